@@ -1,0 +1,214 @@
+/*
+ * pvf.h -- C ABI of libpvf: one Plan-Verify-Fill (PVF) denoising round for a masked
+ * diffusion language model on one AMD MI355X (gfx950), and the decode loop around it.
+ *
+ * A round (Algorithm 1 of the paper, one forward per round) is
+ *   forward   : one batched, non-causal transformer pass over the backbone canvas (the
+ *               base branch z_base, Sec. 3) and up to K draft canvases (Eq. plan_branch,
+ *               Sec. 4.3), logits produced only for the rows of the active block and the
+ *               block after it;
+ *   epilogue  : per logits row the top-1 token and its softmax probability (Sec. 3), then
+ *               verify the drafts (Eq. impact_set, Eq. at, Filter 1/2 of Sec. 4.2, the AR
+ *               acceptance set of Sec. 4.3), commit the winner, and from the winner's own
+ *               predictions apply the confidence threshold (Sec. 2) and propose the next
+ *               drafts (Sec. 4.1 planning candidates, else Sec. 4.3 AR candidates).
+ *
+ * Conventions
+ *   - "dev" pointers are device memory owned by the CALLER; "host" pointers are host
+ *     memory.  The library owns only the workspace inside pvf_ctx.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls
+ *     enqueue work on it and return without synchronising unless stated otherwise.
+ *   - Every call returns a pvf_status; nothing throws or aborts across this boundary.
+ *     Arguments are validated before any launch.  pvf_last_error() gives a message for
+ *     the last failing call on that context (or on the calling thread if ctx is NULL).
+ *   - Matrices are row-major.  Weight matrices are [out_features, in_features], i.e.
+ *     y = x * W^T.  dtype 0 = float32, 1 = bfloat16 (storage of weights, activations and
+ *     logits; accumulation is always float32).
+ *   - Canvas positions: [0, prompt_len) prompt, then gen_len generated tokens split into
+ *     gen_len / block_len blocks (App. A.1).  T = prompt_len + gen_len.
+ *   - Window: the R = min(2*block_len, gen_len) canvas positions starting at the first
+ *     position of the active block; row r of a canvas is position
+ *     prompt_len + k_active*block_len + r.  Rows whose position is >= T do not exist:
+ *     their summaries are conf = 0, tok = -1.
+ */
+#ifndef PVF_H
+#define PVF_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  PVF_OK = 0,
+  PVF_EINVAL = -1,   /* bad argument value                                   */
+  PVF_ESHAPE = -2,   /* shape exceeds what the context was created for       */
+  PVF_ENOMEM = -3,   /* workspace allocation failed                          */
+  PVF_EHIP = -4,     /* a HIP runtime call failed (message has the HIP text) */
+  PVF_ENOTIMPL = -5  /* combination not supported by this build              */
+} pvf_status;
+
+enum { PVF_F32 = 0, PVF_BF16 = 1 };
+enum { PVF_ROUTE_NONE = 0, PVF_ROUTE_PLAN = 1, PVF_ROUTE_AR = 2 };
+enum { PVF_ROUTES_PLAN = 1, PVF_ROUTES_AR = 2 };
+
+typedef struct pvf_ctx pvf_ctx;
+
+/* Denoiser P_theta (Sec. 2).  The paper does not fix the architecture; this library runs a
+ * pre-norm bidirectional transformer: RMSNorm, rotary embedding (dimension i paired with
+ * i + d_head/2, angle pos * rope_theta^(-2i/d_head)), full multi-head attention with no
+ * mask, SwiGLU FFN, untied output head. */
+typedef struct {
+  int32_t n_layers, d_model, n_heads, d_ff, vocab;
+  int32_t dtype;        /* PVF_F32 or PVF_BF16 */
+  float rms_eps, rope_theta;
+  int32_t mask_id;      /* id of the absorbing [MASK] token, in [0, vocab) */
+} pvf_model_cfg;
+
+/* Hyper-parameters of Algorithm 1 (hyper-parameter table of the appendix). */
+typedef struct {
+  float tau_high;       /* commit threshold (Sec. 2)                                  */
+  float tau_plan_lo;    /* planning band [lo, hi) (Sec. 4.1); lo <= hi <= tau_high     */
+  float tau_plan_hi;
+  float tau_ar_lo;      /* AR fallback threshold (Sec. 4.3)                            */
+  float logit_scale;    /* > 0; probabilities are softmax(logit_scale * logits)        */
+  int32_t K;            /* draft budget per canvas group, 0..PVF_MAX_K                 */
+  int32_t block_len;    /* tokens per block; gen_len % block_len == 0                  */
+  int32_t prompt_len;
+  int32_t gen_len;
+  int32_t routes;       /* bit 0 planning route, bit 1 AR route; 0 = threshold decoding */
+  int32_t n_sparse;     /* early cross-block revelation threshold N_s; must be 0       */
+} pvf_decode_cfg;
+
+#define PVF_MAX_K 16
+#define PVF_MAX_SUMMARIES 8192   /* (1+K) * R must not exceed this */
+
+/* Weights, all dev, in cfg.dtype.  Per-layer entries are HOST arrays of n_layers dev pointers.
+ *   embed [vocab, d]   out_head [vocab, d]   final_norm [d]
+ *   attn_norm [d]  wqkv [3d, d] (rows: q | k | v)  wo [d, d]
+ *   ffn_norm [d]   w_gate_up [2*d_ff, d] (rows: gate | up)  w_down [d, d_ff]
+ * The library keeps the pointers (not copies); they must stay valid until pvf_destroy. */
+typedef struct {
+  const void *embed, *out_head, *final_norm;
+  const void *const *attn_norm, *const *wqkv, *const *wo;
+  const void *const *ffn_norm, *const *w_gate_up, *const *w_down;
+} pvf_weights;
+
+/* Decoding state of G canvas groups, all dev, read-modify-write by the epilogue.
+ * One group = one backbone canvas plus its draft slots; slot 0 is the backbone. */
+typedef struct {
+  int32_t *canvas;      /* [G, 1+K, T]  in: this round's batch X_0..X_K; out: next batch  */
+  int32_t *n_drafts;    /* [G]          in: K_t of this batch;  out: K_{t+1}              */
+  int32_t *draft_route; /* [G]          PVF_ROUTE_* of the drafts (in/out)                */
+  int32_t *fill_pos;    /* [G, K]       canvas position of candidate j (in/out)           */
+  int32_t *fill_tok;    /* [G, K]       token of candidate j (in/out).  Planning draft j  */
+                        /*              = backbone + fill j; AR draft k = backbone +      */
+                        /*              fills 1..k                                        */
+  int32_t *k_active;    /* [G]          index of the active block (in/out)                */
+  float   *conf;        /* [G, 1+K, R]  out: top-1 probability per window row             */
+  int32_t *tok;         /* [G, 1+K, R]  out: top-1 token per window row                   */
+  uint8_t *accept;      /* [G, K]       out: A_j (planning) / pass bit (AR) of THIS batch */
+  int32_t *winner;      /* [G]          out: 0 = base branch, else the committed slot     */
+  int32_t *n_commit;    /* [G, 3]       out: tokens committed this round by the           */
+                        /*              threshold / planning route / AR route             */
+  int32_t *done;        /* [G]          in/out: 1 once the canvas holds no mask; a done    */
+                        /*              group is skipped                                  */
+} pvf_state;
+
+typedef struct {
+  int32_t rounds;       /* forward passes issued (NFE of the batch)                        */
+  int32_t seq_forwards; /* canvases forwarded, summed over rounds                          */
+  int64_t n_base, n_plan, n_ar;   /* tokens committed by each route, summed over groups   */
+  int64_t drafts_proposed, drafts_accepted;
+  double  ms_total;     /* wall time of the loop (host clock, includes the per-round sync) */
+} pvf_stats;
+
+/* ---- context ------------------------------------------------------------------------- */
+
+/* Allocates the activation workspace for at most max_seqs canvases of at most max_T tokens
+ * with at most max_rows logits rows each.  Returns PVF_ENOMEM / PVF_EHIP on failure. */
+pvf_status pvf_create(pvf_ctx **out, const pvf_model_cfg *model, const pvf_weights *weights,
+                      int32_t max_seqs, int32_t max_T, int32_t max_rows);
+void pvf_destroy(pvf_ctx *ctx);
+/* Static or context-owned string, never freed by the caller. */
+const char *pvf_last_error(const pvf_ctx *ctx);
+/* Bytes of device workspace the context holds. */
+int64_t pvf_workspace_bytes(const pvf_ctx *ctx);
+
+/* ---- the four calls of the path -------------------------------------------------------- */
+
+/* P_theta(. | canvas) for S canvases in one batch (Sec. 4.1, "one batched forward pass").
+ *   tokens  dev int32 [S, T]
+ *   row_pos dev int32 [S, R]  canvas positions whose logits are wanted; a negative entry
+ *                             yields a row of zeros
+ *   logits  dev [S, R, vocab] in model dtype, unscaled (logit_scale is applied by the
+ *                             epilogue). */
+pvf_status pvf_forward(pvf_ctx *ctx, void *stream, const int32_t *tokens, int32_t S, int32_t T,
+                       const int32_t *row_pos, int32_t R, void *logits);
+
+/* Decision epilogue over logits [G, 1+K, R, vocab] (logits_dtype PVF_F32 / PVF_BF16), R the
+ * window size defined above.  Slots above n_drafts[g] and done groups are not read.
+ * plan_bitmap: dev, ceil(vocab/32) words, bit (id & 31) of word (id >> 5) set iff id is in
+ * the planning vocabulary P^plan (Sec. 3).  ctx may be NULL (no workspace is used). */
+pvf_status pvf_epilogue(pvf_ctx *ctx, void *stream, const void *logits, int32_t logits_dtype,
+                        int32_t G, int32_t vocab, int32_t mask_id, const uint32_t *plan_bitmap,
+                        const pvf_decode_cfg *cfg, const pvf_state *state);
+
+/* forward + epilogue on the same stream, no synchronisation in between.  n_seq_host: if
+ * > 0, the caller's count of live canvases sum_g (done[g] ? 0 : 1 + n_drafts[g]) as read
+ * from the state after the previous round; only those are forwarded.  If <= 0 all
+ * G*(1+K) slots are forwarded (same results, more work). */
+pvf_status pvf_round(pvf_ctx *ctx, void *stream, int32_t G, const uint32_t *plan_bitmap,
+                     const pvf_decode_cfg *cfg, const pvf_state *state, int32_t n_seq_host);
+
+/* y_0 = [prompt | MASK^gen_len] in every slot, no drafts, k_active = 0, done = 0.
+ *   prompt dev int32 [G, prompt_len]; must not contain mask_id (not checked on device). */
+pvf_status pvf_state_init(pvf_ctx *ctx, void *stream, const int32_t *prompt, int32_t G,
+                          const pvf_decode_cfg *cfg, const pvf_state *state);
+
+/* Algorithm 1 to completion for G groups: pvf_state_init, then pvf_round until every group
+ * is done.  Synchronises the stream once per round to read 2*G status words.
+ *   out_tokens dev int32 [G, T]; stats host (may be NULL). */
+pvf_status pvf_decode(pvf_ctx *ctx, void *stream, const int32_t *prompt, int32_t G,
+                      const uint32_t *plan_bitmap, const pvf_decode_cfg *cfg,
+                      const pvf_state *state, int32_t *out_tokens, pvf_stats *stats);
+
+/* ---- building blocks, exported so that each kernel can be checked and timed alone ------- */
+
+/* Stage 1 of the epilogue alone (Sec. 3: y-hat and p per position): for each of n_rows
+ * rows of `logits` [n_rows, vocab], over all ids except mask_id,
+ *   tok = lowest id attaining max_w x_w,  conf = 1 / sum_w exp(x_w - max x),
+ *   x_w = logit_scale * logit_w.   conf dev float32 [n_rows], tok dev int32 [n_rows]. */
+pvf_status pvf_stage1(void *stream, const void *logits, int32_t logits_dtype, int64_t n_rows,
+                      int32_t vocab, int32_t mask_id, float logit_scale, float *conf,
+                      int32_t *tok);
+
+/* C[M,N] = A[M,K] * W[N,K]^T (+ residual[M,N]); all dev, dtype PVF_F32 / PVF_BF16.
+ * residual may be NULL and may alias C. */
+pvf_status pvf_gemm(void *stream, int32_t dtype, const void *A, const void *W, void *C,
+                    const void *residual, int32_t M, int32_t N, int32_t K);
+
+/* act[M, ff] = silu(A W_gate^T) * (A W_up^T) with W [2*ff, K] (rows gate | up). */
+pvf_status pvf_gemm_swiglu(void *stream, int32_t dtype, const void *A, const void *W, void *act,
+                           int32_t M, int32_t ff, int32_t K);
+
+/* out[M, d] = x / sqrt(mean(x^2) + eps) * gain. */
+pvf_status pvf_rmsnorm(void *stream, int32_t dtype, const void *x, const void *gain, void *out,
+                       int32_t M, int32_t d, float eps);
+
+/* In-place rotary embedding of the q and k thirds of qkv [S*T, 3*d] (row m is canvas
+ * position m % T), then out[S*T, d] = softmax(q k^T / sqrt(d_head)) v per canvas and head,
+ * over all T keys. */
+pvf_status pvf_rope_attention(void *stream, int32_t dtype, void *qkv, void *out, int32_t S,
+                              int32_t T, int32_t n_heads, int32_t d_head, float rope_theta);
+
+/* Fills dev buffer with n values ~ N(0, std^2) (+ mean) from a counter-based generator;
+ * used to materialise random-init weights of benchmark shapes directly in HBM. */
+pvf_status pvf_fill_normal(void *stream, int32_t dtype, void *dst, int64_t n, uint64_t seed,
+                           float mean, float std);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PVF_H */

@@ -234,12 +234,16 @@ class RoundInfo:
     n_ar: int = 0
     impact: List[int] = field(default_factory=list)
     c_total: List[float] = field(default_factory=list)
-    margin: float = np.inf           # smallest distance of any decision from flipping
+    margin: float = np.inf           # smallest relative distance of any decision from flipping
     committed: Optional[np.ndarray] = None   # y_t: the canvas right after the verify/commit step
 
 
 def _margin_cmp(info: RoundInfo, a: float, b: float) -> None:
-    info.margin = min(info.margin, abs(float(a) - float(b)))
+    """Records how far a comparison a <> b is from flipping, relative to the larger operand
+    (a perturbation of the logits by e moves a probability p by about 2 e p (1 - p))."""
+    a, b = float(a), float(b)
+    den = max(abs(a), abs(b))
+    info.margin = min(info.margin, abs(a - b) / den if den > 0 else 0.0)
 
 
 def branch_canvases(y: np.ndarray, drafts: Drafts) -> List[np.ndarray]:

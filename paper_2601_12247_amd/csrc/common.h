@@ -1,0 +1,110 @@
+// Shared declarations of libpvf's translation units (host side + small device helpers).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "pvf.h"
+
+namespace pvf {
+
+typedef __bf16 bf16_t;
+
+// ---- error reporting ---------------------------------------------------------------
+// Records a printf-style message on the context (or in a thread-local slot if ctx == NULL).
+void set_error(pvf_ctx *ctx, const char *fmt, ...);
+
+#define PVF_HIP_CHECK(ctx, call)                                                         \
+  do {                                                                                   \
+    hipError_t e__ = (call);                                                             \
+    if (e__ != hipSuccess) {                                                             \
+      ::pvf::set_error(ctx, "%s: %s (%s:%d)", #call, hipGetErrorString(e__), __FILE__,  \
+                       __LINE__);                                                        \
+      return PVF_EHIP;                                                                   \
+    }                                                                                    \
+  } while (0)
+
+#define PVF_LAUNCH_CHECK(ctx, what) PVF_HIP_CHECK(ctx, hipGetLastError())
+
+#define PVF_REQUIRE(ctx, cond, code, ...)                                                \
+  do {                                                                                   \
+    if (!(cond)) {                                                                       \
+      ::pvf::set_error(ctx, __VA_ARGS__);                                                \
+      return code;                                                                       \
+    }                                                                                    \
+  } while (0)
+
+// ---- device helpers ------------------------------------------------------------------
+__device__ __forceinline__ float bf16_bits_to_float(uint32_t bits16) {
+  return __uint_as_float(bits16 << 16);
+}
+__device__ __forceinline__ float to_float(float x) { return x; }
+__device__ __forceinline__ float to_float(bf16_t x) { return (float)x; }
+template <typename T> __device__ __forceinline__ T from_float(float x);
+template <> __device__ __forceinline__ float from_float<float>(float x) { return x; }
+template <> __device__ __forceinline__ bf16_t from_float<bf16_t>(float x) { return (bf16_t)x; }
+
+constexpr int kWave = 64;
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = kWave / 2; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = kWave / 2; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, kWave));
+  return v;
+}
+
+// ---- kernel launchers (each defined in the .hip file holding its kernels) -------------
+// Row filter of the epilogue's stage 1: which logits rows exist and where their summary goes.
+struct RowFilter {
+  const int32_t *n_drafts;  // [G] or NULL (NULL: every row is live, out row = in row)
+  const int32_t *done;      // [G]
+  const int32_t *k_active;  // [G]
+  const int32_t *seq_slot;  // [n_seq] compact sequence -> slot g*(1+K)+j, or NULL (identity)
+  int32_t slots_per_group;  // 1+K
+  int32_t R, prompt_len, block_len, T;
+};
+
+pvf_status launch_stage1(pvf_ctx *ctx, hipStream_t s, const void *logits, int dtype,
+                         int64_t n_rows, int vocab, int mask_id, float scale,
+                         const RowFilter &rf, float *conf, int32_t *tok);
+
+pvf_status launch_stage2(pvf_ctx *ctx, hipStream_t s, int G, int vocab, int mask_id,
+                         const uint32_t *plan_bitmap, const pvf_decode_cfg &cfg,
+                         const pvf_state &st);
+
+pvf_status launch_state_init(pvf_ctx *ctx, hipStream_t s, const int32_t *prompt, int G,
+                             int mask_id, const pvf_decode_cfg &cfg, const pvf_state &st);
+
+// builds seq_slot[] and row_pos[] for a round; n_seq entries are written (padding repeats slot 0)
+pvf_status launch_build_batch(pvf_ctx *ctx, hipStream_t s, int G, int n_seq,
+                              const pvf_decode_cfg &cfg, const pvf_state &st,
+                              int32_t *seq_slot, int32_t *row_pos);
+
+pvf_status launch_copy_out(pvf_ctx *ctx, hipStream_t s, int G, int K, int T,
+                           const int32_t *canvas, int32_t *out_tokens);
+
+// forward building blocks
+pvf_status launch_embed(pvf_ctx *ctx, hipStream_t s, int dtype, const void *embed,
+                        const int32_t *tokens, const int32_t *seq_slot, int S, int T, int d,
+                        int vocab, void *h);
+pvf_status launch_rmsnorm(pvf_ctx *ctx, hipStream_t s, int dtype, const void *x,
+                          const void *gain, void *out, int M, int d, float eps);
+pvf_status launch_gather_rows(pvf_ctx *ctx, hipStream_t s, int dtype, const void *h,
+                              const int32_t *row_pos, int S, int T, int R, int d, void *out);
+pvf_status launch_rope(pvf_ctx *ctx, hipStream_t s, int dtype, void *qkv, int M, int T,
+                       int n_heads, int d_head, const float2 *cos_sin);
+pvf_status launch_attention(pvf_ctx *ctx, hipStream_t s, int dtype, const void *qkv, void *out,
+                            int S, int T, int n_heads, int d_head);
+enum GemmEpilogue { kEpiStore = 0, kEpiResidual = 1, kEpiSwiglu = 2 };
+// C[M,N] = A[M,K] W[N,K]^T; kEpiResidual adds residual[M,N]; kEpiSwiglu: W is [2N,K] (gate|up),
+// C[M,N] = silu(gate) * up.
+pvf_status launch_gemm(pvf_ctx *ctx, hipStream_t s, int dtype, GemmEpilogue epi, const void *A,
+                       const void *W, void *C, const void *residual, int M, int N, int K);
+pvf_status launch_fill_normal(pvf_ctx *ctx, hipStream_t s, int dtype, void *dst, int64_t n,
+                              uint64_t seed, float mean, float std);
+
+}  // namespace pvf

@@ -1,0 +1,220 @@
+// Memory-bound pieces of the denoiser forward: embedding gather, RMSNorm, window-row gather,
+// rotary embedding, and a counter-based normal generator for random-init weights.
+// The paper treats P_theta as a black box (Sec. 2); the architecture is this library's.
+#include "common.h"
+
+namespace pvf {
+namespace {
+
+// 16-byte vector of T
+template <typename T> struct Pack { static constexpr int N = 16 / sizeof(T); };
+
+// ---- embedding: h[s*T + t, :] = E[tokens[slot(s)*T + t], :] ----------------------------
+template <typename T>
+__global__ void __launch_bounds__(256)
+embed_kernel(const T *__restrict__ embed, const int32_t *__restrict__ tokens,
+             const int32_t *__restrict__ seq_slot, int T_len, int d, int vocab, T *__restrict__ h) {
+  const int64_t m = blockIdx.x;
+  const int s = (int)(m / T_len), t = (int)(m % T_len);
+  const int slot = seq_slot ? seq_slot[s] : s;
+  int id = tokens[(int64_t)slot * T_len + t];
+  id = id < 0 ? 0 : (id >= vocab ? vocab - 1 : id);   // ids are validated on the host; stay in bounds regardless
+  constexpr int N = Pack<T>::N;
+  const uint4 *src = reinterpret_cast<const uint4 *>(embed + (int64_t)id * d);
+  uint4 *dst = reinterpret_cast<uint4 *>(h + m * d);
+  for (int i = threadIdx.x; i < d / N; i += blockDim.x) dst[i] = src[i];
+}
+
+// ---- RMSNorm: out = x * rsqrt(mean(x^2) + eps) * gain, one row per block ---------------
+template <typename T>
+__global__ void __launch_bounds__(256)
+rmsnorm_kernel(const T *__restrict__ x, const T *__restrict__ gain, T *__restrict__ out, int d,
+               float eps) {
+  const int64_t m = blockIdx.x;
+  const T *xr = x + m * d;
+  float ss = 0.f;
+  for (int i = threadIdx.x; i < d; i += blockDim.x) { const float v = to_float(xr[i]); ss += v * v; }
+  __shared__ float s_part[4];
+  ss = wave_sum(ss);
+  if (threadIdx.x % kWave == 0) s_part[threadIdx.x / kWave] = ss;
+  __syncthreads();
+  const float tot = s_part[0] + s_part[1] + s_part[2] + s_part[3];
+  const float r = rsqrtf(tot / (float)d + eps);
+  for (int i = threadIdx.x; i < d; i += blockDim.x)
+    out[m * d + i] = from_float<T>(to_float(xr[i]) * r * to_float(gain[i]));
+}
+
+// vectorised bf16 variant (d % 8 == 0): 16-byte loads, values kept in registers between passes
+template <int MAXV>
+__global__ void __launch_bounds__(256)
+rmsnorm_bf16_vec_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ gain,
+                        bf16_t *__restrict__ out, int d, float eps) {
+  const int64_t m = blockIdx.x;
+  const uint4 *xr = reinterpret_cast<const uint4 *>(x + m * d);
+  const uint4 *gr = reinterpret_cast<const uint4 *>(gain);
+  uint4 *orow = reinterpret_cast<uint4 *>(out + m * d);
+  const int nvec = d / 8;
+  uint4 v[MAXV];
+  float ss = 0.f;
+#pragma unroll
+  for (int k = 0; k < MAXV; ++k) {
+    const int i = threadIdx.x + k * 256;
+    if (i < nvec) {
+      v[k] = xr[i];
+      const uint32_t w[4] = {v[k].x, v[k].y, v[k].z, v[k].w};
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const float a = __uint_as_float(w[q] << 16), b = __uint_as_float(w[q] & 0xffff0000u);
+        ss += a * a + b * b;
+      }
+    }
+  }
+  __shared__ float s_part[4];
+  ss = wave_sum(ss);
+  if (threadIdx.x % kWave == 0) s_part[threadIdx.x / kWave] = ss;
+  __syncthreads();
+  const float r = rsqrtf((s_part[0] + s_part[1] + s_part[2] + s_part[3]) / (float)d + eps);
+#pragma unroll
+  for (int k = 0; k < MAXV; ++k) {
+    const int i = threadIdx.x + k * 256;
+    if (i < nvec) {
+      const uint4 g4 = gr[i];
+      const uint32_t w[4] = {v[k].x, v[k].y, v[k].z, v[k].w};
+      const uint32_t gw[4] = {g4.x, g4.y, g4.z, g4.w};
+      uint32_t o[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const float a = __uint_as_float(w[q] << 16) * r * __uint_as_float(gw[q] << 16);
+        const float b = __uint_as_float(w[q] & 0xffff0000u) * r * __uint_as_float(gw[q] & 0xffff0000u);
+        const bf16_t ab = (bf16_t)a, bb = (bf16_t)b;
+        o[q] = (uint32_t)__builtin_bit_cast(uint16_t, ab) | ((uint32_t)__builtin_bit_cast(uint16_t, bb) << 16);
+      }
+      orow[i] = make_uint4(o[0], o[1], o[2], o[3]);
+    }
+  }
+}
+
+// ---- window-row gather: out[s*R + r, :] = h[s*T + row_pos[s*R + r], :] (zeros if < 0) ---
+template <typename T>
+__global__ void __launch_bounds__(256)
+gather_rows_kernel(const T *__restrict__ h, const int32_t *__restrict__ row_pos, int T_len, int R,
+                   int d, T *__restrict__ out) {
+  const int64_t row = blockIdx.x;
+  const int s = (int)(row / R);
+  const int pos = row_pos[row];
+  constexpr int N = Pack<T>::N;
+  uint4 *dst = reinterpret_cast<uint4 *>(out + row * d);
+  if (pos < 0 || pos >= T_len) {
+    for (int i = threadIdx.x; i < d / N; i += blockDim.x) dst[i] = make_uint4(0, 0, 0, 0);
+    return;
+  }
+  const uint4 *src = reinterpret_cast<const uint4 *>(h + ((int64_t)s * T_len + pos) * d);
+  for (int i = threadIdx.x; i < d / N; i += blockDim.x) dst[i] = src[i];
+}
+
+// ---- rotary embedding, in place on the q and k thirds of qkv [M, 3d] --------------------
+// pair (i, i + dh/2) of each head at canvas position m % T is rotated by cos_sin[pos][i].
+template <typename T>
+__global__ void __launch_bounds__(256)
+rope_kernel(T *__restrict__ qkv, int T_len, int n_heads, int dh, const float2 *__restrict__ cos_sin) {
+  const int64_t m = blockIdx.x;
+  const int pos = (int)(m % T_len);
+  const int half = dh / 2, d = n_heads * dh;
+  T *row = qkv + m * 3 * (int64_t)d;
+  for (int idx = threadIdx.x; idx < 2 * n_heads * half; idx += blockDim.x) {
+    const int i = idx % half, hh = idx / half;        // hh in [0, 2*n_heads): q heads then k heads
+    T *p = row + (int64_t)hh * dh;                    // k third starts right after the q third
+    const float2 cs = cos_sin[(int64_t)pos * half + i];
+    const float a = to_float(p[i]), b = to_float(p[i + half]);
+    p[i] = from_float<T>(a * cs.x - b * cs.y);
+    p[i + half] = from_float<T>(b * cs.x + a * cs.y);
+  }
+}
+
+// ---- N(mean, std^2) fill from a counter-based generator ---------------------------------
+__device__ __forceinline__ uint64_t mix64(uint64_t z) {
+  z += 0x9E3779B97F4A7C15ull;
+  z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+  z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+  return z ^ (z >> 31);
+}
+template <typename T>
+__global__ void fill_normal_kernel(T *__restrict__ dst, int64_t n, uint64_t seed, float mean, float std) {
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; 2 * p < n; p += stride) {
+    const uint64_t r = mix64(mix64(seed) ^ (uint64_t)p);
+    const float u1 = ((float)(uint32_t)(r >> 40) + 0.5f) * (1.0f / 16777216.0f);     // (0,1)
+    const float u2 = (float)(uint32_t)((r >> 8) & 0xffffffu) * (1.0f / 16777216.0f);
+    const float rad = sqrtf(-2.0f * __logf(u1));
+    float sn, cs;
+    __sincosf(6.283185307179586f * u2, &sn, &cs);
+    dst[2 * p] = from_float<T>(mean + std * rad * cs);
+    if (2 * p + 1 < n) dst[2 * p + 1] = from_float<T>(mean + std * rad * sn);
+  }
+}
+
+}  // namespace
+
+pvf_status launch_embed(pvf_ctx *ctx, hipStream_t s, int dtype, const void *embed,
+                        const int32_t *tokens, const int32_t *seq_slot, int S, int T, int d,
+                        int vocab, void *h) {
+  const unsigned M = (unsigned)(S * (int64_t)T);
+  if (dtype == PVF_BF16)
+    embed_kernel<bf16_t><<<M, 256, 0, s>>>((const bf16_t *)embed, tokens, seq_slot, T, d, vocab, (bf16_t *)h);
+  else
+    embed_kernel<float><<<M, 256, 0, s>>>((const float *)embed, tokens, seq_slot, T, d, vocab, (float *)h);
+  PVF_LAUNCH_CHECK(ctx, "embed");
+  return PVF_OK;
+}
+
+pvf_status launch_rmsnorm(pvf_ctx *ctx, hipStream_t s, int dtype, const void *x, const void *gain,
+                          void *out, int M, int d, float eps) {
+  if (M == 0) return PVF_OK;
+  if (dtype == PVF_BF16) {
+    if (d % 8 == 0 && d / 8 <= 256 * 2)
+      rmsnorm_bf16_vec_kernel<2><<<M, 256, 0, s>>>((const bf16_t *)x, (const bf16_t *)gain, (bf16_t *)out, d, eps);
+    else
+      rmsnorm_kernel<bf16_t><<<M, 256, 0, s>>>((const bf16_t *)x, (const bf16_t *)gain, (bf16_t *)out, d, eps);
+  } else {
+    rmsnorm_kernel<float><<<M, 256, 0, s>>>((const float *)x, (const float *)gain, (float *)out, d, eps);
+  }
+  PVF_LAUNCH_CHECK(ctx, "rmsnorm");
+  return PVF_OK;
+}
+
+pvf_status launch_gather_rows(pvf_ctx *ctx, hipStream_t s, int dtype, const void *h,
+                              const int32_t *row_pos, int S, int T, int R, int d, void *out) {
+  const unsigned rows = (unsigned)(S * (int64_t)R);
+  if (rows == 0) return PVF_OK;
+  if (dtype == PVF_BF16)
+    gather_rows_kernel<bf16_t><<<rows, 256, 0, s>>>((const bf16_t *)h, row_pos, T, R, d, (bf16_t *)out);
+  else
+    gather_rows_kernel<float><<<rows, 256, 0, s>>>((const float *)h, row_pos, T, R, d, (float *)out);
+  PVF_LAUNCH_CHECK(ctx, "gather_rows");
+  return PVF_OK;
+}
+
+pvf_status launch_rope(pvf_ctx *ctx, hipStream_t s, int dtype, void *qkv, int M, int T,
+                       int n_heads, int d_head, const float2 *cos_sin) {
+  if (M == 0) return PVF_OK;
+  if (dtype == PVF_BF16)
+    rope_kernel<bf16_t><<<M, 256, 0, s>>>((bf16_t *)qkv, T, n_heads, d_head, cos_sin);
+  else
+    rope_kernel<float><<<M, 256, 0, s>>>((float *)qkv, T, n_heads, d_head, cos_sin);
+  PVF_LAUNCH_CHECK(ctx, "rope");
+  return PVF_OK;
+}
+
+pvf_status launch_fill_normal(pvf_ctx *ctx, hipStream_t s, int dtype, void *dst, int64_t n,
+                              uint64_t seed, float mean, float std) {
+  if (n <= 0) return PVF_OK;
+  const int blocks = (int)((n / 2 + 255) / 256 < 65536 ? (n / 2 + 255) / 256 + 1 : 65536);
+  if (dtype == PVF_BF16)
+    fill_normal_kernel<bf16_t><<<blocks, 256, 0, s>>>((bf16_t *)dst, n, seed, mean, std);
+  else
+    fill_normal_kernel<float><<<blocks, 256, 0, s>>>((float *)dst, n, seed, mean, std);
+  PVF_LAUNCH_CHECK(ctx, "fill_normal");
+  return PVF_OK;
+}
+
+}  // namespace pvf

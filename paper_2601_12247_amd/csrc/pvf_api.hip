@@ -1,0 +1,439 @@
+// C-ABI entry points of libpvf: argument validation, workspace, and the order of launches of
+// one PVF round (Algorithm 1 with one batched forward per round) and of the decode loop.
+#include "common.h"
+
+#include <chrono>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <string>
+#include <vector>
+
+struct pvf_ctx {
+  pvf_model_cfg model;
+  pvf_weights w;                       // top-level pointers
+  std::vector<const void *> attn_norm, wqkv, wo, ffn_norm, w_gate_up, w_down;
+  int max_seqs = 0, max_T = 0, max_rows = 0;
+  size_t esize = 4;
+  // workspace (device)
+  void *h = nullptr, *xn = nullptr, *qkv = nullptr, *att = nullptr, *act = nullptr;
+  void *hrows = nullptr, *logits = nullptr;
+  int32_t *seq_slot = nullptr, *row_pos = nullptr;
+  float2 *cos_sin = nullptr;           // [max_T, d_head/2]
+  int32_t *status_host = nullptr;      // pinned, 2*G words per round
+  int status_cap = 0;
+  int64_t ws_bytes = 0;
+  char err[512] = {0};
+};
+
+namespace pvf {
+
+static thread_local char g_err[512] = {0};
+
+void set_error(pvf_ctx *ctx, const char *fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(ctx ? ctx->err : g_err, 512, fmt, ap);
+  va_end(ap);
+}
+
+// ---- dispatch between the MFMA kernels and the plain ones -------------------------------
+pvf_status launch_gemm_simple(pvf_ctx *, hipStream_t, int, GemmEpilogue, const void *, const void *,
+                              void *, const void *, int, int, int);
+pvf_status launch_attention_simple(pvf_ctx *, hipStream_t, int, const void *, void *, int, int, int, int);
+bool gemm_mfma_supported(int dtype, GemmEpilogue epi, int M, int N, int K);
+pvf_status launch_gemm_mfma(pvf_ctx *, hipStream_t, GemmEpilogue, const void *, const void *, void *,
+                            const void *, int, int, int);
+bool attention_mfma_supported(int dtype, int T, int d_head);
+pvf_status launch_attention_mfma(pvf_ctx *, hipStream_t, const void *, void *, int, int, int, int);
+
+static bool force_simple() {
+  static const bool v = [] { const char *e = getenv("PVF_FORCE_SIMPLE"); return e && e[0] == '1'; }();
+  return v;
+}
+
+pvf_status launch_gemm(pvf_ctx *ctx, hipStream_t s, int dtype, GemmEpilogue epi, const void *A,
+                       const void *W, void *C, const void *residual, int M, int N, int K) {
+  if (!force_simple() && gemm_mfma_supported(dtype, epi, M, N, K))
+    return launch_gemm_mfma(ctx, s, epi, A, W, C, residual, M, N, K);
+  return launch_gemm_simple(ctx, s, dtype, epi, A, W, C, residual, M, N, K);
+}
+
+pvf_status launch_attention(pvf_ctx *ctx, hipStream_t s, int dtype, const void *qkv, void *out,
+                            int S, int T, int n_heads, int d_head) {
+  if (!force_simple() && attention_mfma_supported(dtype, T, d_head))
+    return launch_attention_mfma(ctx, s, qkv, out, S, T, n_heads, d_head);
+  return launch_attention_simple(ctx, s, dtype, qkv, out, S, T, n_heads, d_head);
+}
+
+// ---- validation -----------------------------------------------------------------------
+static int window_rows(const pvf_decode_cfg &c) {
+  return (2 * c.block_len < c.gen_len) ? 2 * c.block_len : c.gen_len;
+}
+
+static pvf_status check_decode_cfg(pvf_ctx *ctx, const pvf_decode_cfg *c, int vocab, int mask_id) {
+  PVF_REQUIRE(ctx, c != nullptr, PVF_EINVAL, "decode cfg is NULL");
+  PVF_REQUIRE(ctx, c->K >= 0 && c->K <= PVF_MAX_K, PVF_EINVAL, "K=%d outside [0,%d]", c->K, PVF_MAX_K);
+  PVF_REQUIRE(ctx, c->block_len > 0 && c->gen_len > 0 && c->prompt_len >= 0, PVF_EINVAL,
+              "block_len=%d gen_len=%d prompt_len=%d", c->block_len, c->gen_len, c->prompt_len);
+  PVF_REQUIRE(ctx, c->gen_len % c->block_len == 0, PVF_EINVAL, "gen_len %% block_len != 0 (%d, %d)", c->gen_len, c->block_len);
+  PVF_REQUIRE(ctx, c->tau_plan_lo <= c->tau_plan_hi && c->tau_plan_hi <= c->tau_high, PVF_EINVAL,
+              "need tau_plan_lo <= tau_plan_hi <= tau_high (%g, %g, %g)", c->tau_plan_lo, c->tau_plan_hi, c->tau_high);
+  PVF_REQUIRE(ctx, c->logit_scale > 0.f && std::isfinite(c->logit_scale), PVF_EINVAL, "logit_scale=%g must be positive", c->logit_scale);
+  PVF_REQUIRE(ctx, (c->routes & ~3) == 0, PVF_EINVAL, "routes=%d has unknown bits", c->routes);
+  PVF_REQUIRE(ctx, c->n_sparse == 0, PVF_ENOTIMPL, "n_sparse=%d: early cross-block revelation is not built", c->n_sparse);
+  PVF_REQUIRE(ctx, mask_id >= 0 && mask_id < vocab, PVF_EINVAL, "mask_id=%d outside [0,%d)", mask_id, vocab);
+  PVF_REQUIRE(ctx, (int64_t)(1 + c->K) * window_rows(*c) <= PVF_MAX_SUMMARIES, PVF_ESHAPE,
+              "(1+K)*R = %lld exceeds %d", (long long)(1 + c->K) * window_rows(*c), PVF_MAX_SUMMARIES);
+  return PVF_OK;
+}
+
+static pvf_status check_state(pvf_ctx *ctx, const pvf_state *st) {
+  PVF_REQUIRE(ctx, st != nullptr, PVF_EINVAL, "state is NULL");
+  PVF_REQUIRE(ctx, st->canvas && st->n_drafts && st->draft_route && st->fill_pos && st->fill_tok &&
+                  st->k_active && st->conf && st->tok && st->accept && st->winner && st->n_commit && st->done,
+              PVF_EINVAL, "state has a NULL member");
+  return PVF_OK;
+}
+
+}  // namespace pvf
+
+using namespace pvf;
+
+// =========================================================================================
+// context
+// =========================================================================================
+static void free_ws(pvf_ctx *c) {
+  void *ptrs[] = {c->h, c->xn, c->qkv, c->att, c->act, c->hrows, c->logits, c->seq_slot, c->row_pos, c->cos_sin};
+  for (void *p : ptrs) if (p) (void)hipFree(p);
+  if (c->status_host) (void)hipHostFree(c->status_host);
+}
+
+extern "C" pvf_status pvf_create(pvf_ctx **out, const pvf_model_cfg *m, const pvf_weights *w,
+                                 int32_t max_seqs, int32_t max_T, int32_t max_rows) {
+  PVF_REQUIRE(nullptr, out && m && w, PVF_EINVAL, "pvf_create: NULL argument");
+  *out = nullptr;
+  PVF_REQUIRE(nullptr, m->dtype == PVF_F32 || m->dtype == PVF_BF16, PVF_EINVAL, "dtype=%d", m->dtype);
+  PVF_REQUIRE(nullptr, m->n_layers > 0 && m->d_model > 0 && m->n_heads > 0 && m->d_ff > 0 && m->vocab > 1,
+              PVF_EINVAL, "non-positive model dimension");
+  PVF_REQUIRE(nullptr, m->d_model % m->n_heads == 0 && (m->d_model / m->n_heads) % 2 == 0, PVF_EINVAL,
+              "d_model=%d must split into n_heads=%d even-sized heads", m->d_model, m->n_heads);
+  PVF_REQUIRE(nullptr, m->d_model % 8 == 0 && m->d_ff % 8 == 0, PVF_EINVAL, "d_model and d_ff must be multiples of 8");
+  PVF_REQUIRE(nullptr, m->mask_id >= 0 && m->mask_id < m->vocab, PVF_EINVAL, "mask_id=%d outside [0,%d)", m->mask_id, m->vocab);
+  PVF_REQUIRE(nullptr, m->rms_eps >= 0.f && m->rope_theta > 0.f, PVF_EINVAL, "rms_eps / rope_theta");
+  PVF_REQUIRE(nullptr, max_seqs > 0 && max_T > 0 && max_rows > 0 && max_rows <= max_T, PVF_EINVAL,
+              "max_seqs=%d max_T=%d max_rows=%d", max_seqs, max_T, max_rows);
+  PVF_REQUIRE(nullptr, w->embed && w->out_head && w->final_norm && w->attn_norm && w->wqkv && w->wo &&
+                  w->ffn_norm && w->w_gate_up && w->w_down, PVF_EINVAL, "weights has a NULL member");
+  for (int l = 0; l < m->n_layers; ++l)
+    PVF_REQUIRE(nullptr, w->attn_norm[l] && w->wqkv[l] && w->wo[l] && w->ffn_norm[l] && w->w_gate_up[l] && w->w_down[l],
+                PVF_EINVAL, "layer %d has a NULL weight", l);
+
+  pvf_ctx *c = new (std::nothrow) pvf_ctx();
+  PVF_REQUIRE(nullptr, c != nullptr, PVF_ENOMEM, "host allocation failed");
+  c->model = *m;
+  c->w = *w;
+  const int L = m->n_layers;
+  c->attn_norm.assign(w->attn_norm, w->attn_norm + L);
+  c->wqkv.assign(w->wqkv, w->wqkv + L);
+  c->wo.assign(w->wo, w->wo + L);
+  c->ffn_norm.assign(w->ffn_norm, w->ffn_norm + L);
+  c->w_gate_up.assign(w->w_gate_up, w->w_gate_up + L);
+  c->w_down.assign(w->w_down, w->w_down + L);
+  c->max_seqs = max_seqs; c->max_T = max_T; c->max_rows = max_rows;
+  c->esize = m->dtype == PVF_BF16 ? 2 : 4;
+
+  const int64_t M = (int64_t)max_seqs * max_T, d = m->d_model, ff = m->d_ff;
+  const int64_t rows = (int64_t)max_seqs * max_rows;
+  const int half = m->d_model / m->n_heads / 2;
+  struct { void **p; int64_t bytes; } req[] = {
+      {&c->h, M * d * (int64_t)c->esize},       {&c->xn, M * d * (int64_t)c->esize},
+      {&c->qkv, M * 3 * d * (int64_t)c->esize}, {&c->att, M * d * (int64_t)c->esize},
+      {&c->act, M * ff * (int64_t)c->esize},    {&c->hrows, rows * d * (int64_t)c->esize},
+      {&c->logits, rows * (int64_t)m->vocab * (int64_t)c->esize},
+      {(void **)&c->seq_slot, (int64_t)max_seqs * 4}, {(void **)&c->row_pos, rows * 4},
+      {(void **)&c->cos_sin, (int64_t)max_T * half * 8}};
+  for (auto &r : req) {
+    hipError_t e = hipMalloc(r.p, (size_t)r.bytes);
+    if (e != hipSuccess) {
+      set_error(nullptr, "pvf_create: hipMalloc(%lld bytes) failed: %s", (long long)r.bytes, hipGetErrorString(e));
+      free_ws(c);
+      delete c;
+      return e == hipErrorOutOfMemory ? PVF_ENOMEM : PVF_EHIP;
+    }
+    c->ws_bytes += r.bytes;
+  }
+  // rotary table in double precision on the host: angle = pos * theta^(-2i/d_head)
+  {
+    std::vector<float2> tab((size_t)max_T * half);
+    const int dh = 2 * half;
+    for (int i = 0; i < half; ++i) {
+      const double inv = std::pow((double)m->rope_theta, -2.0 * i / dh);
+      for (int t = 0; t < max_T; ++t) {
+        const double a = (double)t * inv;
+        tab[(size_t)t * half + i] = make_float2((float)std::cos(a), (float)std::sin(a));
+      }
+    }
+    hipError_t e = hipMemcpy(c->cos_sin, tab.data(), tab.size() * sizeof(float2), hipMemcpyHostToDevice);
+    if (e != hipSuccess) {
+      set_error(nullptr, "pvf_create: rotary table upload failed: %s", hipGetErrorString(e));
+      free_ws(c);
+      delete c;
+      return PVF_EHIP;
+    }
+  }
+  *out = c;
+  return PVF_OK;
+}
+
+extern "C" void pvf_destroy(pvf_ctx *ctx) {
+  if (!ctx) return;
+  free_ws(ctx);
+  delete ctx;
+}
+
+extern "C" const char *pvf_last_error(const pvf_ctx *ctx) { return ctx ? ctx->err : pvf::g_err; }
+extern "C" int64_t pvf_workspace_bytes(const pvf_ctx *ctx) { return ctx ? ctx->ws_bytes : 0; }
+
+// =========================================================================================
+// forward
+// =========================================================================================
+// tokens: [*, T] rows addressed through seq_slot (NULL = identity).  Writes logits [S, R, V].
+static pvf_status forward_impl(pvf_ctx *c, hipStream_t s, const int32_t *tokens,
+                               const int32_t *seq_slot, int S, int T, const int32_t *row_pos,
+                               int R, void *logits) {
+  const pvf_model_cfg &m = c->model;
+  const int d = m.d_model, H = m.n_heads, dh = d / H, ff = m.d_ff, dt = m.dtype;
+  const int M = S * T;
+  pvf_status st;
+#define RUN(x) do { st = (x); if (st != PVF_OK) return st; } while (0)
+  RUN(launch_embed(c, s, dt, c->w.embed, tokens, seq_slot, S, T, d, m.vocab, c->h));
+  for (int l = 0; l < m.n_layers; ++l) {
+    RUN(launch_rmsnorm(c, s, dt, c->h, c->attn_norm[l], c->xn, M, d, m.rms_eps));
+    RUN(launch_gemm(c, s, dt, kEpiStore, c->xn, c->wqkv[l], c->qkv, nullptr, M, 3 * d, d));
+    RUN(launch_rope(c, s, dt, c->qkv, M, T, H, dh, c->cos_sin));
+    RUN(launch_attention(c, s, dt, c->qkv, c->att, S, T, H, dh));
+    RUN(launch_gemm(c, s, dt, kEpiResidual, c->att, c->wo[l], c->h, c->h, M, d, d));
+    RUN(launch_rmsnorm(c, s, dt, c->h, c->ffn_norm[l], c->xn, M, d, m.rms_eps));
+    RUN(launch_gemm(c, s, dt, kEpiSwiglu, c->xn, c->w_gate_up[l], c->act, nullptr, M, ff, d));
+    RUN(launch_gemm(c, s, dt, kEpiResidual, c->act, c->w_down[l], c->h, c->h, M, d, ff));
+  }
+  RUN(launch_gather_rows(c, s, dt, c->h, row_pos, S, T, R, d, c->hrows));
+  RUN(launch_rmsnorm(c, s, dt, c->hrows, c->w.final_norm, c->hrows, S * R, d, m.rms_eps));
+  RUN(launch_gemm(c, s, dt, kEpiStore, c->hrows, c->w.out_head, logits, nullptr, S * R, m.vocab, d));
+#undef RUN
+  return PVF_OK;
+}
+
+extern "C" pvf_status pvf_forward(pvf_ctx *ctx, void *stream, const int32_t *tokens, int32_t S,
+                                  int32_t T, const int32_t *row_pos, int32_t R, void *logits) {
+  PVF_REQUIRE(nullptr, ctx != nullptr, PVF_EINVAL, "pvf_forward: ctx is NULL");
+  PVF_REQUIRE(ctx, tokens && row_pos && logits, PVF_EINVAL, "pvf_forward: NULL pointer");
+  PVF_REQUIRE(ctx, S >= 0 && T > 0 && R >= 0, PVF_EINVAL, "pvf_forward: S=%d T=%d R=%d", S, T, R);
+  PVF_REQUIRE(ctx, S <= ctx->max_seqs && T <= ctx->max_T && R <= ctx->max_rows, PVF_ESHAPE,
+              "pvf_forward: S=%d T=%d R=%d exceed the context (%d, %d, %d)", S, T, R, ctx->max_seqs, ctx->max_T, ctx->max_rows);
+  if (S == 0 || R == 0) return PVF_OK;
+  return forward_impl(ctx, (hipStream_t)stream, tokens, nullptr, S, T, row_pos, R, logits);
+}
+
+// =========================================================================================
+// epilogue
+// =========================================================================================
+extern "C" pvf_status pvf_stage1(void *stream, const void *logits, int32_t logits_dtype,
+                                 int64_t n_rows, int32_t vocab, int32_t mask_id, float logit_scale,
+                                 float *conf, int32_t *tok) {
+  PVF_REQUIRE(nullptr, n_rows == 0 || (logits && conf && tok), PVF_EINVAL, "pvf_stage1: NULL pointer");
+  PVF_REQUIRE(nullptr, logits_dtype == PVF_F32 || logits_dtype == PVF_BF16, PVF_EINVAL, "pvf_stage1: dtype=%d", logits_dtype);
+  PVF_REQUIRE(nullptr, n_rows >= 0 && vocab > 1, PVF_EINVAL, "pvf_stage1: n_rows=%lld vocab=%d", (long long)n_rows, vocab);
+  PVF_REQUIRE(nullptr, mask_id >= 0 && mask_id < vocab, PVF_EINVAL, "pvf_stage1: mask_id=%d outside [0,%d)", mask_id, vocab);
+  PVF_REQUIRE(nullptr, logit_scale > 0.f && std::isfinite(logit_scale), PVF_EINVAL, "pvf_stage1: logit_scale=%g", logit_scale);
+  RowFilter rf{};
+  return launch_stage1(nullptr, (hipStream_t)stream, logits, logits_dtype, n_rows, vocab, mask_id, logit_scale, rf, conf, tok);
+}
+
+static RowFilter make_filter(const pvf_decode_cfg &cfg, const pvf_state &st, const int32_t *seq_slot) {
+  RowFilter rf;
+  rf.n_drafts = st.n_drafts; rf.done = st.done; rf.k_active = st.k_active; rf.seq_slot = seq_slot;
+  rf.slots_per_group = 1 + cfg.K; rf.R = window_rows(cfg);
+  rf.prompt_len = cfg.prompt_len; rf.block_len = cfg.block_len; rf.T = cfg.prompt_len + cfg.gen_len;
+  return rf;
+}
+
+extern "C" pvf_status pvf_epilogue(pvf_ctx *ctx, void *stream, const void *logits, int32_t logits_dtype,
+                                   int32_t G, int32_t vocab, int32_t mask_id, const uint32_t *plan_bitmap,
+                                   const pvf_decode_cfg *cfg, const pvf_state *state) {
+  pvf_status st = check_decode_cfg(ctx, cfg, vocab, mask_id);
+  if (st != PVF_OK) return st;
+  if ((st = check_state(ctx, state)) != PVF_OK) return st;
+  PVF_REQUIRE(ctx, logits && plan_bitmap, PVF_EINVAL, "pvf_epilogue: NULL pointer");
+  PVF_REQUIRE(ctx, logits_dtype == PVF_F32 || logits_dtype == PVF_BF16, PVF_EINVAL, "pvf_epilogue: dtype=%d", logits_dtype);
+  PVF_REQUIRE(ctx, G >= 0, PVF_EINVAL, "pvf_epilogue: G=%d", G);
+  if (G == 0) return PVF_OK;
+  hipStream_t s = (hipStream_t)stream;
+  const RowFilter rf = make_filter(*cfg, *state, nullptr);
+  const int64_t n_rows = (int64_t)G * (1 + cfg->K) * rf.R;
+  st = launch_stage1(ctx, s, logits, logits_dtype, n_rows, vocab, mask_id, cfg->logit_scale, rf, state->conf, state->tok);
+  if (st != PVF_OK) return st;
+  return launch_stage2(ctx, s, G, vocab, mask_id, plan_bitmap, *cfg, *state);
+}
+
+// =========================================================================================
+// round, state init, decode
+// =========================================================================================
+static pvf_status check_round(pvf_ctx *ctx, int G, const uint32_t *plan_bitmap, const pvf_decode_cfg *cfg,
+                              const pvf_state *state) {
+  PVF_REQUIRE(nullptr, ctx != nullptr, PVF_EINVAL, "ctx is NULL");
+  pvf_status st = check_decode_cfg(ctx, cfg, ctx->model.vocab, ctx->model.mask_id);
+  if (st != PVF_OK) return st;
+  if ((st = check_state(ctx, state)) != PVF_OK) return st;
+  PVF_REQUIRE(ctx, plan_bitmap != nullptr, PVF_EINVAL, "plan_bitmap is NULL");
+  PVF_REQUIRE(ctx, G > 0, PVF_EINVAL, "G=%d", G);
+  const int T = cfg->prompt_len + cfg->gen_len;
+  PVF_REQUIRE(ctx, (int64_t)G * (1 + cfg->K) <= ctx->max_seqs && T <= ctx->max_T && window_rows(*cfg) <= ctx->max_rows,
+              PVF_ESHAPE, "G*(1+K)=%d T=%d R=%d exceed the context (%d, %d, %d)", G * (1 + cfg->K), T,
+              window_rows(*cfg), ctx->max_seqs, ctx->max_T, ctx->max_rows);
+  return PVF_OK;
+}
+
+static pvf_status round_impl(pvf_ctx *ctx, hipStream_t s, int G, const uint32_t *plan_bitmap,
+                             const pvf_decode_cfg &cfg, const pvf_state &state, int n_seq) {
+  const int T = cfg.prompt_len + cfg.gen_len, R = window_rows(cfg);
+  const int all = G * (1 + cfg.K);
+  if (n_seq <= 0 || n_seq > all) n_seq = all;
+  pvf_status st = launch_build_batch(ctx, s, G, n_seq, cfg, state, ctx->seq_slot, ctx->row_pos);
+  if (st != PVF_OK) return st;
+  st = forward_impl(ctx, s, state.canvas, ctx->seq_slot, n_seq, T, ctx->row_pos, R, ctx->logits);
+  if (st != PVF_OK) return st;
+  const RowFilter rf = make_filter(cfg, state, ctx->seq_slot);
+  st = launch_stage1(ctx, s, ctx->logits, ctx->model.dtype, (int64_t)n_seq * R, ctx->model.vocab,
+                     ctx->model.mask_id, cfg.logit_scale, rf, state.conf, state.tok);
+  if (st != PVF_OK) return st;
+  return launch_stage2(ctx, s, G, ctx->model.vocab, ctx->model.mask_id, plan_bitmap, cfg, state);
+}
+
+extern "C" pvf_status pvf_round(pvf_ctx *ctx, void *stream, int32_t G, const uint32_t *plan_bitmap,
+                                const pvf_decode_cfg *cfg, const pvf_state *state, int32_t n_seq_host) {
+  pvf_status st = check_round(ctx, G, plan_bitmap, cfg, state);
+  if (st != PVF_OK) return st;
+  return round_impl(ctx, (hipStream_t)stream, G, plan_bitmap, *cfg, *state, n_seq_host);
+}
+
+extern "C" pvf_status pvf_state_init(pvf_ctx *ctx, void *stream, const int32_t *prompt, int32_t G,
+                                     const pvf_decode_cfg *cfg, const pvf_state *state) {
+  PVF_REQUIRE(nullptr, ctx != nullptr, PVF_EINVAL, "ctx is NULL");
+  pvf_status st = check_decode_cfg(ctx, cfg, ctx->model.vocab, ctx->model.mask_id);
+  if (st != PVF_OK) return st;
+  if ((st = check_state(ctx, state)) != PVF_OK) return st;
+  PVF_REQUIRE(ctx, G > 0 && (prompt || cfg->prompt_len == 0), PVF_EINVAL, "pvf_state_init: G=%d prompt=%p", G, (const void *)prompt);
+  return launch_state_init(ctx, (hipStream_t)stream, prompt, G, ctx->model.mask_id, *cfg, *state);
+}
+
+extern "C" pvf_status pvf_decode(pvf_ctx *ctx, void *stream, const int32_t *prompt, int32_t G,
+                                 const uint32_t *plan_bitmap, const pvf_decode_cfg *cfg,
+                                 const pvf_state *state, int32_t *out_tokens, pvf_stats *stats) {
+  pvf_status st = check_round(ctx, G, plan_bitmap, cfg, state);
+  if (st != PVF_OK) return st;
+  PVF_REQUIRE(ctx, out_tokens && (prompt || cfg->prompt_len == 0), PVF_EINVAL, "pvf_decode: NULL pointer");
+  hipStream_t s = (hipStream_t)stream;
+  if (ctx->status_cap < 5 * G) {
+    if (ctx->status_host) (void)hipHostFree(ctx->status_host);
+    ctx->status_host = nullptr;
+    PVF_HIP_CHECK(ctx, hipHostMalloc((void **)&ctx->status_host, (size_t)5 * G * sizeof(int32_t), hipHostMallocDefault));
+    ctx->status_cap = 5 * G;
+  }
+  int32_t *h_done = ctx->status_host, *h_nd = h_done + G, *h_nc = h_nd + G;
+  pvf_stats acc;
+  memset(&acc, 0, sizeof(acc));
+  const auto t0 = std::chrono::steady_clock::now();
+  if ((st = launch_state_init(ctx, s, prompt, G, ctx->model.mask_id, *cfg, *state)) != PVF_OK) return st;
+  int n_seq = G;                                  // first round: backbones only
+  std::vector<int> prev_nd(G, 0);
+  const int max_rounds = cfg->gen_len + 2;        // every round commits at least one token per live group
+  while (n_seq > 0) {
+    PVF_REQUIRE(ctx, acc.rounds < max_rounds, PVF_EINVAL, "pvf_decode: no progress after %d rounds", acc.rounds);
+    if ((st = round_impl(ctx, s, G, plan_bitmap, *cfg, *state, n_seq)) != PVF_OK) return st;
+    acc.rounds += 1;
+    acc.seq_forwards += n_seq;
+    PVF_HIP_CHECK(ctx, hipMemcpyAsync(h_done, state->done, G * sizeof(int32_t), hipMemcpyDeviceToHost, s));
+    PVF_HIP_CHECK(ctx, hipMemcpyAsync(h_nd, state->n_drafts, G * sizeof(int32_t), hipMemcpyDeviceToHost, s));
+    PVF_HIP_CHECK(ctx, hipMemcpyAsync(h_nc, state->n_commit, 3 * G * sizeof(int32_t), hipMemcpyDeviceToHost, s));
+    PVF_HIP_CHECK(ctx, hipStreamSynchronize(s));
+    n_seq = 0;
+    for (int g = 0; g < G; ++g) {
+      acc.n_base += h_nc[3 * g + 0]; acc.n_plan += h_nc[3 * g + 1]; acc.n_ar += h_nc[3 * g + 2];
+      acc.drafts_accepted += (h_nc[3 * g + 1] > 0) + h_nc[3 * g + 2];
+      if (!h_done[g]) { n_seq += 1 + h_nd[g]; acc.drafts_proposed += h_nd[g]; }
+      prev_nd[g] = h_nd[g];
+    }
+  }
+  if ((st = launch_copy_out(ctx, s, G, cfg->K, cfg->prompt_len + cfg->gen_len, state->canvas, out_tokens)) != PVF_OK) return st;
+  PVF_HIP_CHECK(ctx, hipStreamSynchronize(s));
+  acc.ms_total = std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t0).count();
+  if (stats) *stats = acc;
+  return PVF_OK;
+}
+
+// =========================================================================================
+// building blocks
+// =========================================================================================
+static pvf_status check_dtype(int dtype) {
+  PVF_REQUIRE(nullptr, dtype == PVF_F32 || dtype == PVF_BF16, PVF_EINVAL, "dtype=%d", dtype);
+  return PVF_OK;
+}
+
+extern "C" pvf_status pvf_gemm(void *stream, int32_t dtype, const void *A, const void *W, void *C,
+                               const void *residual, int32_t M, int32_t N, int32_t K) {
+  if (check_dtype(dtype) != PVF_OK) return PVF_EINVAL;
+  PVF_REQUIRE(nullptr, A && W && C && M >= 0 && N >= 0 && K > 0, PVF_EINVAL, "pvf_gemm: bad argument");
+  return launch_gemm(nullptr, (hipStream_t)stream, dtype, residual ? kEpiResidual : kEpiStore, A, W, C, residual, M, N, K);
+}
+
+extern "C" pvf_status pvf_gemm_swiglu(void *stream, int32_t dtype, const void *A, const void *W,
+                                      void *act, int32_t M, int32_t ff, int32_t K) {
+  if (check_dtype(dtype) != PVF_OK) return PVF_EINVAL;
+  PVF_REQUIRE(nullptr, A && W && act && M >= 0 && ff >= 0 && K > 0, PVF_EINVAL, "pvf_gemm_swiglu: bad argument");
+  return launch_gemm(nullptr, (hipStream_t)stream, dtype, kEpiSwiglu, A, W, act, nullptr, M, ff, K);
+}
+
+extern "C" pvf_status pvf_rmsnorm(void *stream, int32_t dtype, const void *x, const void *gain,
+                                  void *out, int32_t M, int32_t d, float eps) {
+  if (check_dtype(dtype) != PVF_OK) return PVF_EINVAL;
+  PVF_REQUIRE(nullptr, x && gain && out && M >= 0 && d > 0, PVF_EINVAL, "pvf_rmsnorm: bad argument");
+  return launch_rmsnorm(nullptr, (hipStream_t)stream, dtype, x, gain, out, M, d, eps);
+}
+
+// Builds the rotary table on the host for this call, so it synchronises the stream and
+// allocates; it exists for tests, the round itself uses the context's table.
+extern "C" pvf_status pvf_rope_attention(void *stream, int32_t dtype, void *qkv, void *out, int32_t S,
+                                         int32_t T, int32_t n_heads, int32_t d_head, float rope_theta) {
+  if (check_dtype(dtype) != PVF_OK) return PVF_EINVAL;
+  PVF_REQUIRE(nullptr, qkv && out && S >= 0 && T > 0 && n_heads > 0 && d_head > 0 && d_head % 2 == 0 && rope_theta > 0.f,
+              PVF_EINVAL, "pvf_rope_attention: bad argument");
+  if (S == 0) return PVF_OK;
+  hipStream_t s = (hipStream_t)stream;
+  const int half = d_head / 2;
+  std::vector<float2> tab((size_t)T * half);
+  for (int i = 0; i < half; ++i) {
+    const double inv = std::pow((double)rope_theta, -2.0 * i / d_head);
+    for (int t = 0; t < T; ++t)
+      tab[(size_t)t * half + i] = make_float2((float)std::cos(t * inv), (float)std::sin(t * inv));
+  }
+  float2 *dev = nullptr;
+  PVF_HIP_CHECK(nullptr, hipMalloc((void **)&dev, tab.size() * sizeof(float2)));
+  hipError_t e = hipMemcpy(dev, tab.data(), tab.size() * sizeof(float2), hipMemcpyHostToDevice);
+  pvf_status st = PVF_OK;
+  if (e != hipSuccess) { set_error(nullptr, "rotary table upload: %s", hipGetErrorString(e)); st = PVF_EHIP; }
+  if (st == PVF_OK) st = launch_rope(nullptr, s, dtype, qkv, S * T, T, n_heads, d_head, dev);
+  if (st == PVF_OK) st = launch_attention(nullptr, s, dtype, qkv, out, S, T, n_heads, d_head);
+  (void)hipStreamSynchronize(s);
+  (void)hipFree(dev);
+  return st;
+}
+
+extern "C" pvf_status pvf_fill_normal(void *stream, int32_t dtype, void *dst, int64_t n, uint64_t seed,
+                                      float mean, float std) {
+  if (check_dtype(dtype) != PVF_OK) return PVF_EINVAL;
+  PVF_REQUIRE(nullptr, dst && n >= 0, PVF_EINVAL, "pvf_fill_normal: bad argument");
+  return launch_fill_normal(nullptr, (hipStream_t)stream, dtype, dst, n, seed, mean, std);
+}
