@@ -136,6 +136,19 @@ const char *pvf_last_error(const pvf_ctx *ctx);
 /* Bytes of device workspace the context holds. */
 int64_t pvf_workspace_bytes(const pvf_ctx *ctx);
 
+/* ---- per-kernel timing ------------------------------------------------------------------
+ * Between pvf_profile_begin and pvf_profile_end every GEMM, attention (rotary + attention) and
+ * epilogue stage-1 launch the context makes is bracketed by a pair of HIP events on the launch
+ * stream.  pvf_profile_end synchronises the stream and returns, per category, the summed
+ * event-to-event time, the algorithmic work (flops / bytes) and the number of launches. */
+enum { PVF_PROF_GEMM = 0, PVF_PROF_ATTENTION = 1, PVF_PROF_STAGE1 = 2, PVF_PROF_NCAT = 3 };
+typedef struct {
+  double ms[PVF_PROF_NCAT], flops[PVF_PROF_NCAT], bytes[PVF_PROF_NCAT];
+  int64_t launches[PVF_PROF_NCAT];
+} pvf_profile;
+pvf_status pvf_profile_begin(pvf_ctx *ctx);
+pvf_status pvf_profile_end(pvf_ctx *ctx, void *stream, pvf_profile *out);
+
 /* ---- the four calls of the path -------------------------------------------------------- */
 
 /* P_theta(. | canvas) for S canvases in one batch (Sec. 4.1, "one batched forward pass").

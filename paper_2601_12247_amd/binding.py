@@ -23,7 +23,8 @@ STATUS = {0: "PVF_OK", -1: "PVF_EINVAL", -2: "PVF_ESHAPE", -3: "PVF_ENOMEM", -4:
           -5: "PVF_ENOTIMPL"}
 
 # every symbol include/pvf.h declares
-EXPORTS = ["pvf_create", "pvf_destroy", "pvf_last_error", "pvf_workspace_bytes", "pvf_forward",
+EXPORTS = ["pvf_create", "pvf_destroy", "pvf_last_error", "pvf_workspace_bytes", "pvf_profile_begin",
+           "pvf_profile_end", "pvf_forward",
            "pvf_epilogue", "pvf_round", "pvf_state_init", "pvf_decode", "pvf_stage1", "pvf_gemm",
            "pvf_gemm_swiglu", "pvf_rmsnorm", "pvf_rope_attention", "pvf_fill_normal"]
 
@@ -66,6 +67,11 @@ class StatsC(C.Structure):
                 ("drafts_accepted", C.c_int64), ("ms_total", C.c_double)]
 
 
+class ProfileC(C.Structure):
+    _fields_ = [("ms", C.c_double * 3), ("flops", C.c_double * 3), ("bytes", C.c_double * 3),
+                ("launches", C.c_int64 * 3)]
+
+
 _lib = None
 
 
@@ -82,6 +88,8 @@ def lib() -> C.CDLL:
         L.pvf_workspace_bytes.argtypes = [C.c_void_p]
         L.pvf_destroy.restype = None
         L.pvf_destroy.argtypes = [C.c_void_p]
+        L.pvf_profile_begin.argtypes = [C.c_void_p]
+        L.pvf_profile_end.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(ProfileC)]
         L.pvf_create.argtypes = [C.POINTER(C.c_void_p), C.POINTER(ModelCfgC), C.POINTER(WeightsC),
                                  C.c_int32, C.c_int32, C.c_int32]
         L.pvf_forward.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32,
@@ -238,6 +246,15 @@ class Context:
     @property
     def workspace_bytes(self) -> int:
         return lib().pvf_workspace_bytes(self.handle)
+
+    def profile_begin(self) -> None:
+        _check(lib().pvf_profile_begin(self.handle), self.handle)
+
+    def profile_end(self) -> Dict[str, Dict[str, float]]:
+        p = ProfileC()
+        _check(lib().pvf_profile_end(self.handle, _stream(), C.byref(p)), self.handle)
+        return {name: {"ms": p.ms[i], "flops": p.flops[i], "bytes": p.bytes[i], "launches": p.launches[i]}
+                for i, name in enumerate(("gemm", "attention", "stage1"))}
 
     # ---- the four calls -------------------------------------------------------------
     def forward(self, tokens: torch.Tensor, row_pos: torch.Tensor) -> torch.Tensor:

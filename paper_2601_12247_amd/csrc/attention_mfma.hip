@@ -1,9 +1,232 @@
-// bf16 non-causal attention on the MFMA matrix cores (placeholder until the kernel lands).
+// Non-causal attention on the CDNA4 matrix cores (bf16, d_head = 128): every query of a
+// canvas attends to all T positions of the same canvas, masked or not -- the denoiser sees
+// the whole canvas at once (Sec. 2).  Flash-style: K / V tiles of 64 keys are staged in LDS,
+// the softmax is kept online in registers and the T x T score matrix is never materialised.
+//
+// Layout choices
+//   * one workgroup = 128 queries of one (canvas, head); 4 waves x 32 queries;
+//   * scores are computed transposed, S^T = K Q^T (MFMA "A" = K rows, "B" = Q rows), so a lane
+//     owns ONE query (column lane%32) and 32 of the tile's 64 keys in registers: the softmax
+//     max / sum are register loops plus one exchange with lane^32;
+//   * O^T = V^T P^T: the probabilities a lane just produced are already the "B" operand of
+//     the second product (the contraction index is permuted identically on both operands), and
+//     every O^T accumulator of a lane belongs to that lane's query, so rescaling is lane-local;
+//   * V is read key-contiguous, from a [canvas, head, d_head, T] copy written by the rotary
+//     kernel; K and V^T tiles go global -> LDS directly, XOR-swizzled against bank conflicts,
+//     double-buffered.
 #include "common.h"
+
 namespace pvf {
-bool attention_mfma_supported(int, int, int) { return false; }
-pvf_status launch_attention_mfma(pvf_ctx *ctx, hipStream_t, const void *, void *, int, int, int, int) {
-  set_error(ctx, "attention_mfma: not built");
-  return PVF_ENOTIMPL;
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef __attribute__((address_space(1))) const void gptr_t;
+typedef __attribute__((address_space(3))) void lptr_t;
+
+constexpr int DH = 128, TQ = 128, TK = 64;
+constexpr int kKTile = TK * DH * 2;          // 16 KB, [key][d] rows of 256 B
+constexpr int kVTile = DH * TK * 2;          // 16 KB, [d][key] rows of 128 B
+constexpr int kStage = kKTile + kVTile;
+constexpr float kLog2e = 1.4426950408889634f;
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+__global__ void __launch_bounds__(256)
+attention_mfma_kernel(const bf16_t *__restrict__ qkv, const bf16_t *__restrict__ vt,
+                      bf16_t *__restrict__ out, int T, int H) {
+  __shared__ __attribute__((aligned(1024))) unsigned char lds[2 * kStage];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int fr = lane & 31, fh = lane >> 5;
+  const int q0 = blockIdx.x * TQ, head = blockIdx.y, seq = blockIdx.z;
+  const int d = H * DH;
+  const int64_t row0 = (int64_t)seq * T;
+  const bf16_t *qb = qkv + row0 * 3 * d + (int64_t)head * DH;
+  const bf16_t *kb = qb + d;
+  const bf16_t *vtb = vt + ((int64_t)seq * H + head) * DH * T;
+
+  // ---- Q fragments: "B" operand, column = query, k-chunk = 8 consecutive d ----
+  const int qrow = min(q0 + wave * 32 + fr, T - 1);
+  bf16x8 qf[8];
+#pragma unroll
+  for (int ks = 0; ks < 8; ++ks)
+    qf[ks] = *reinterpret_cast<const bf16x8 *>(qb + (int64_t)qrow * 3 * d + ks * 16 + fh * 8);
+
+  // ---- global -> LDS addressing (see file header) ----
+  // K tile: slot s = i*256 + tid -> key s/16, position s%16, chunk = position ^ (key & 15)
+  // V^T tile: slot s -> d-row s/8, position s%8, chunk = position ^ ((row >> 1) & 7)
+  const bf16_t *k_src[4], *v_src[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int s = i * 256 + tid;
+    const int key = s >> 4, kc = (s & 15) ^ (key & 15);
+    k_src[i] = kb + (int64_t)key * 3 * d + kc * 8;
+    const int vr = s >> 3, vc = (s & 7) ^ ((vr >> 1) & 7);
+    v_src[i] = vtb + (int64_t)vr * T + vc * 8;
+  }
+  auto issue_loads = [&](int kt, int buf) {
+    unsigned char *dst = lds + buf * kStage + wave * 1024;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      __builtin_amdgcn_global_load_lds((gptr_t *)(k_src[i] + (int64_t)kt * TK * 3 * d), (lptr_t *)(dst + i * 4096), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((gptr_t *)(v_src[i] + kt * TK), (lptr_t *)(dst + kKTile + i * 4096), 16, 0, 0);
+    }
+  };
+
+  floatx16 o[4];                      // O^T: [d tile][..], column = this lane's query
+#pragma unroll
+  for (int t = 0; t < 4; ++t)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) o[t][e] = 0.f;
+  float m_run = -INFINITY, l_run = 0.f;
+  const float c = kLog2e / sqrtf((float)DH);
+
+  const int nk = T / TK;
+  issue_loads(0, 0);
+  for (int kt = 0; kt < nk; ++kt) {
+    __builtin_amdgcn_s_waitcnt(0x0f70);          // vmcnt(0)
+    __syncthreads();
+    if (kt + 1 < nk) issue_loads(kt + 1, (kt + 1) & 1);
+    const unsigned char *ks_ = lds + (kt & 1) * kStage;
+    const unsigned char *vs_ = ks_ + kKTile;
+
+    // ---- S^T = K Q^T : 2 key sub-tiles x 8 k-steps ----
+    floatx16 s[2];
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) s[t][e] = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) {
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        const int key = t * 32 + fr;
+        const bf16x8 kf = *reinterpret_cast<const bf16x8 *>(ks_ + key * 256 + (((ks * 2 + fh) ^ (key & 15)) << 4));
+        s[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], s[t], 0, 0, 0);
+      }
+    }
+    // ---- online softmax for this lane's query ----
+    float mx = s[0][0];
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) mx = fmaxf(mx, s[t][e]);
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    const float m_new = fmaxf(m_run, mx);
+    const float alpha = fast_exp2((m_run - m_new) * c);      // first tile: exp2(-inf) = 0
+    const float nmc = -m_new * c;
+    float psum = 0.f;
+    bf16x8 pf[4];                                            // "B" operand of the 4 key k-steps
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int u = 0; u < 2; ++u)                            // k-step u of sub-tile t: register groups 2u, 2u+1
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const float p = fast_exp2(fmaf(s[t][8 * u + e], c, nmc));
+          psum += p;
+          pf[2 * t + u][e] = (bf16_t)p;
+        }
+    psum += __shfl_xor(psum, 32, 64);
+    l_run = l_run * alpha + psum;
+    m_run = m_new;
+    if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
+#pragma unroll
+      for (int t = 0; t < 4; ++t)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) o[t][e] *= alpha;
+    }
+    // ---- O^T += V^T P^T : 4 d tiles x 4 key k-steps.  k slot (fh, e) of k-step ks2 is key
+    //      16*ks2 + 4*fh + e (e < 4) or 16*ks2 + 8 + 4*fh + (e - 4): the order P came out in ----
+#pragma unroll
+    for (int ks2 = 0; ks2 < 4; ++ks2) {
+#pragma unroll
+      for (int t = 0; t < 4; ++t) {
+        const int vr = t * 32 + fr;
+        const int swz = (vr >> 1) & 7;
+        const unsigned char *rowp = vs_ + vr * 128 + fh * 8;
+        const bf16x4 lo = *reinterpret_cast<const bf16x4 *>(rowp + (((2 * ks2) ^ swz) << 4));
+        const bf16x4 hi = *reinterpret_cast<const bf16x4 *>(rowp + (((2 * ks2 + 1) ^ swz) << 4));
+        const bf16x8 vf = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+        o[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[ks2], o[t], 0, 0, 0);
+      }
+    }
+  }
+
+  // ---- out[q][head*128 + d]: lane holds 4 consecutive d per accumulator group ----
+  const int q = q0 + wave * 32 + fr;
+  if (q < T) {
+    const float inv = 1.0f / l_run;
+    bf16_t *orow = out + (row0 + q) * d + (int64_t)head * DH;
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        bf16x4 v;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) v[j] = (bf16_t)(o[t][4 * i + j] * inv);
+        *reinterpret_cast<bf16x4 *>(orow + t * 32 + 8 * i + 4 * fh) = v;
+      }
+  }
 }
+
+// Rotary embedding of q and k in place (pair (i, i + 64) of each head) and the key-contiguous
+// copy of v:  vt[canvas][head][d][t] = v[canvas*T + t][head*128 + d].  One block = 64 positions
+// of one (canvas, head).
+__global__ void __launch_bounds__(256)
+rope_vt_kernel(bf16_t *__restrict__ qkv, bf16_t *__restrict__ vt, int T, int H,
+               const float2 *__restrict__ cos_sin) {
+  __shared__ bf16_t tile[DH][64 + 2];
+  const int t0 = blockIdx.x * 64, head = blockIdx.y, seq = blockIdx.z;
+  const int d = H * DH;
+  const int tid = threadIdx.x;
+  bf16_t *base = qkv + ((int64_t)seq * T + t0) * 3 * d + (int64_t)head * DH;
+  // rotate q and k: 64 positions x 2 tensors x 64 pairs
+  for (int idx = tid; idx < 64 * 2 * 64; idx += 256) {
+    const int i = idx & 63, which = (idx >> 6) & 1, tt = idx >> 7;
+    bf16_t *p = base + (int64_t)tt * 3 * d + which * d;
+    const float2 cs = cos_sin[(int64_t)(t0 + tt) * 64 + i];
+    const float a = (float)p[i], b = (float)p[i + 64];
+    p[i] = (bf16_t)(a * cs.x - b * cs.y);
+    p[i + 64] = (bf16_t)(b * cs.x + a * cs.y);
+  }
+  // transpose v through LDS
+  for (int idx = tid; idx < 64 * DH; idx += 256) {
+    const int dd = idx & 127, tt = idx >> 7;
+    tile[dd][tt] = base[(int64_t)tt * 3 * d + 2 * d + dd];
+  }
+  __syncthreads();
+  bf16_t *vb = vt + ((int64_t)seq * H + head) * DH * T + t0;
+  for (int idx = tid; idx < DH * 64; idx += 256) {
+    const int tt = idx & 63, dd = idx >> 6;
+    vb[(int64_t)dd * T + tt] = tile[dd][tt];
+  }
+}
+
+}  // namespace
+
+bool attention_mfma_supported(int dtype, int T, int d_head) {
+  return dtype == PVF_BF16 && d_head == DH && T >= TK && T % TK == 0;
+}
+
+// qkv must already be rotated and vt filled (launch_rope_vt).
+pvf_status launch_attention_mfma(pvf_ctx *ctx, hipStream_t s, const void *qkv, const void *vt,
+                                 void *out, int S, int T, int n_heads) {
+  if (S == 0) return PVF_OK;
+  const dim3 grid((T + TQ - 1) / TQ, n_heads, S);
+  attention_mfma_kernel<<<grid, 256, 0, s>>>((const bf16_t *)qkv, (const bf16_t *)vt, (bf16_t *)out, T, n_heads);
+  PVF_LAUNCH_CHECK(ctx, "attention_mfma");
+  return PVF_OK;
+}
+
+pvf_status launch_rope_vt(pvf_ctx *ctx, hipStream_t s, void *qkv, void *vt, int S, int T,
+                          int n_heads, const float2 *cos_sin) {
+  if (S == 0) return PVF_OK;
+  const dim3 grid(T / 64, n_heads, S);
+  rope_vt_kernel<<<grid, 256, 0, s>>>((bf16_t *)qkv, (bf16_t *)vt, T, n_heads, cos_sin);
+  PVF_LAUNCH_CHECK(ctx, "rope_vt");
+  return PVF_OK;
+}
+
 }  // namespace pvf

@@ -1,8 +1,11 @@
 // Non-causal multi-head attention, plain version: out = softmax(q k^T / sqrt(dh)) v over all
 // T keys of the same canvas, no mask of any kind (the denoiser sees the whole canvas, Sec. 2).
 // One block = 8 queries of one (canvas, head); the full score rows live in LDS.  Any d_head,
-// any dtype; this is the float32 path and the fallback of the MFMA kernel.
+// any dtype; this is the float32 path (dot products and sums in float64) and the fallback of
+// the MFMA kernel (float32 accumulation).
 #include "common.h"
+
+#include <type_traits>
 
 namespace pvf {
 namespace {
@@ -13,6 +16,8 @@ template <typename T>
 __global__ void __launch_bounds__(256)
 attention_simple_kernel(const T *__restrict__ qkv, T *__restrict__ out, int T_len, int n_heads,
                         int dh, float inv_sqrt_dh) {
+  using Acc = typename std::conditional<std::is_same<T, float>::value, double, float>::type;
+  constexpr bool kPrecise = std::is_same<T, float>::value;
   extern __shared__ float smem[];
   float *s_q = smem;                 // [TQ][dh]
   float *s_p = smem + TQ * dh;       // [TQ][T_len]
@@ -32,9 +37,9 @@ attention_simple_kernel(const T *__restrict__ qkv, T *__restrict__ out, int T_le
   for (int i = tid; i < nq * T_len; i += 256) {
     const int k = i / nq, q = i % nq;
     const T *kr = kb + (int64_t)k * 3 * d;
-    float acc = 0.f;
-    for (int c = 0; c < dh; ++c) acc = fmaf(s_q[q * dh + c], to_float(kr[c]), acc);
-    s_p[q * T_len + k] = acc * inv_sqrt_dh;
+    Acc acc = 0;
+    for (int c = 0; c < dh; ++c) acc += (Acc)s_q[q * dh + c] * (Acc)to_float(kr[c]);
+    s_p[q * T_len + k] = (float)(acc * (Acc)inv_sqrt_dh);
   }
   __syncthreads();
   const int lane = tid % kWave, wid = tid / kWave;
@@ -44,7 +49,10 @@ attention_simple_kernel(const T *__restrict__ qkv, T *__restrict__ out, int T_le
     for (int k = lane; k < T_len; k += kWave) m = fmaxf(m, pr[k]);
     m = wave_max(m);
     float z = 0.f;
-    for (int k = lane; k < T_len; k += kWave) { const float e = __expf(pr[k] - m); pr[k] = e; z += e; }
+    for (int k = lane; k < T_len; k += kWave) {
+      const float e = kPrecise ? expf(pr[k] - m) : __expf(pr[k] - m);
+      pr[k] = e; z += e;
+    }
     z = wave_sum(z);
     const float inv = 1.0f / z;
     for (int k = lane; k < T_len; k += kWave) pr[k] *= inv;
@@ -53,9 +61,9 @@ attention_simple_kernel(const T *__restrict__ qkv, T *__restrict__ out, int T_le
   for (int i = tid; i < nq * dh; i += 256) {
     const int q = i / dh, c = i % dh;
     const float *pr = s_p + q * T_len;
-    float acc = 0.f;
-    for (int k = 0; k < T_len; ++k) acc = fmaf(pr[k], to_float(vb[(int64_t)k * 3 * d + c]), acc);
-    out[(row0 + q0 + q) * d + (int64_t)head * dh + c] = from_float<T>(acc);
+    Acc acc = 0;
+    for (int k = 0; k < T_len; ++k) acc += (Acc)pr[k] * (Acc)to_float(vb[(int64_t)k * 3 * d + c]);
+    out[(row0 + q0 + q) * d + (int64_t)head * dh + c] = from_float<T>((float)acc);
   }
 }
 

@@ -97,8 +97,6 @@ pvf_status launch_gather_rows(pvf_ctx *ctx, hipStream_t s, int dtype, const void
                               const int32_t *row_pos, int S, int T, int R, int d, void *out);
 pvf_status launch_rope(pvf_ctx *ctx, hipStream_t s, int dtype, void *qkv, int M, int T,
                        int n_heads, int d_head, const float2 *cos_sin);
-pvf_status launch_attention(pvf_ctx *ctx, hipStream_t s, int dtype, const void *qkv, void *out,
-                            int S, int T, int n_heads, int d_head);
 enum GemmEpilogue { kEpiStore = 0, kEpiResidual = 1, kEpiSwiglu = 2 };
 // C[M,N] = A[M,K] W[N,K]^T; kEpiResidual adds residual[M,N]; kEpiSwiglu: W is [2N,K] (gate|up),
 // C[M,N] = silu(gate) * up.

@@ -39,7 +39,7 @@ rmsnorm_kernel(const T *__restrict__ x, const T *__restrict__ gain, T *__restric
   if (threadIdx.x % kWave == 0) s_part[threadIdx.x / kWave] = ss;
   __syncthreads();
   const float tot = s_part[0] + s_part[1] + s_part[2] + s_part[3];
-  const float r = rsqrtf(tot / (float)d + eps);
+  const float r = 1.0f / sqrtf(tot / (float)d + eps);
   for (int i = threadIdx.x; i < d; i += blockDim.x)
     out[m * d + i] = from_float<T>(to_float(xr[i]) * r * to_float(gain[i]));
 }

@@ -1,14 +1,18 @@
-// Plain LDS-tiled GEMM on the vector ALU:  C[M,N] = A[M,K] * W[N,K]^T  with float32
-// accumulation, any M/N/K.  It is the float32 path of the forward (small parity model) and
-// the fallback for bf16 shapes that the MFMA kernel does not cover.
+// Plain LDS-tiled GEMM on the vector ALU:  C[M,N] = A[M,K] * W[N,K]^T, any M/N/K.  It is the
+// float32 path of the forward (small parity model; accumulates in float64 so that its logits
+// stay within a few float32 ulps of the exact ones) and the fallback for bf16 shapes that
+// the MFMA kernel does not cover (float32 accumulation).
 #include "common.h"
+
+#include <type_traits>
 
 namespace pvf {
 namespace {
 
 constexpr int BM = 64, BN = 64, BK = 16, TM = 4, TN = 4;
 
-__device__ __forceinline__ float silu_f(float g) { return g / (1.0f + __expf(-g)); }
+__device__ __forceinline__ float silu_acc(float g) { return g / (1.0f + __expf(-g)); }
+__device__ __forceinline__ double silu_acc(double g) { return g / (1.0 + exp(-g)); }
 
 template <typename T, int EPI>
 __global__ void __launch_bounds__(256)
@@ -20,7 +24,8 @@ gemm_simple_kernel(const T *__restrict__ A, const T *__restrict__ W, T *__restri
   const int tid = threadIdx.x;
   const int tx = tid % 16, ty = tid / 16;
   const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
-  float acc[TM][TN] = {}, accu[TM][TN] = {};
+  using Acc = typename std::conditional<std::is_same<T, float>::value, double, float>::type;
+  Acc acc[TM][TN] = {}, accu[TM][TN] = {};
 
   for (int k0 = 0; k0 < K; k0 += BK) {
     for (int i = tid; i < BM * BK; i += 256) {
@@ -48,8 +53,8 @@ gemm_simple_kernel(const T *__restrict__ A, const T *__restrict__ W, T *__restri
       for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
-          acc[i][j] = fmaf(a[i], b[j], acc[i][j]);
-          if (EPI == kEpiSwiglu) accu[i][j] = fmaf(a[i], u[j], accu[i][j]);
+          acc[i][j] += (Acc)a[i] * (Acc)b[j];
+          if (EPI == kEpiSwiglu) accu[i][j] += (Acc)a[i] * (Acc)u[j];
         }
     }
     __syncthreads();
@@ -60,10 +65,10 @@ gemm_simple_kernel(const T *__restrict__ A, const T *__restrict__ W, T *__restri
     for (int j = 0; j < TN; ++j) {
       const int gm = m0 + ty * TM + i, gn = n0 + tx * TN + j;
       if (gm >= M || gn >= N) continue;
-      float v = acc[i][j];
-      if (EPI == kEpiResidual) v += to_float(residual[(int64_t)gm * N + gn]);
-      if (EPI == kEpiSwiglu) v = silu_f(v) * accu[i][j];
-      C[(int64_t)gm * N + gn] = from_float<T>(v);
+      Acc v = acc[i][j];
+      if (EPI == kEpiResidual) v += (Acc)to_float(residual[(int64_t)gm * N + gn]);
+      if (EPI == kEpiSwiglu) v = silu_acc(v) * accu[i][j];
+      C[(int64_t)gm * N + gn] = from_float<T>((float)v);
     }
 }
 

@@ -17,7 +17,7 @@ struct pvf_ctx {
   int max_seqs = 0, max_T = 0, max_rows = 0;
   size_t esize = 4;
   // workspace (device)
-  void *h = nullptr, *xn = nullptr, *qkv = nullptr, *att = nullptr, *act = nullptr;
+  void *h = nullptr, *xn = nullptr, *qkv = nullptr, *att = nullptr, *act = nullptr, *vt = nullptr;
   void *hrows = nullptr, *logits = nullptr;
   int32_t *seq_slot = nullptr, *row_pos = nullptr;
   float2 *cos_sin = nullptr;           // [max_T, d_head/2]
@@ -25,6 +25,12 @@ struct pvf_ctx {
   int status_cap = 0;
   int64_t ws_bytes = 0;
   char err[512] = {0};
+  // optional per-kernel timing (pvf_profile_begin / pvf_profile_end)
+  struct ProfRec { int cat; double flops, bytes; hipEvent_t e0, e1; };
+  bool prof_on = false;
+  std::vector<ProfRec> prof;
+  std::vector<hipEvent_t> ev_pool;
+  size_t ev_used = 0;
 };
 
 namespace pvf {
@@ -38,6 +44,28 @@ void set_error(pvf_ctx *ctx, const char *fmt, ...) {
   va_end(ap);
 }
 
+// ---- optional timing of a launch with a pair of HIP events on the launch stream ----------
+struct ProfScope {
+  pvf_ctx *c; hipStream_t s; bool on; hipEvent_t e1 = nullptr;
+  ProfScope(pvf_ctx *ctx, hipStream_t st, int cat, double flops, double bytes) : c(ctx), s(st), on(ctx && ctx->prof_on) {
+    if (!on) return;
+    auto get = [&]() {
+      if (c->ev_used == c->ev_pool.size()) {
+        hipEvent_t e = nullptr;
+        if (hipEventCreate(&e) != hipSuccess) return (hipEvent_t) nullptr;
+        c->ev_pool.push_back(e);
+      }
+      return c->ev_pool[c->ev_used++];
+    };
+    hipEvent_t e0 = get();
+    e1 = get();
+    if (!e0 || !e1) { on = false; return; }
+    (void)hipEventRecord(e0, s);
+    c->prof.push_back({cat, flops, bytes, e0, e1});
+  }
+  ~ProfScope() { if (on) (void)hipEventRecord(e1, s); }
+};
+
 // ---- dispatch between the MFMA kernels and the plain ones -------------------------------
 pvf_status launch_gemm_simple(pvf_ctx *, hipStream_t, int, GemmEpilogue, const void *, const void *,
                               void *, const void *, int, int, int);
@@ -46,7 +74,8 @@ bool gemm_mfma_supported(int dtype, GemmEpilogue epi, int M, int N, int K);
 pvf_status launch_gemm_mfma(pvf_ctx *, hipStream_t, GemmEpilogue, const void *, const void *, void *,
                             const void *, int, int, int);
 bool attention_mfma_supported(int dtype, int T, int d_head);
-pvf_status launch_attention_mfma(pvf_ctx *, hipStream_t, const void *, void *, int, int, int, int);
+pvf_status launch_attention_mfma(pvf_ctx *, hipStream_t, const void *, const void *, void *, int, int, int);
+pvf_status launch_rope_vt(pvf_ctx *, hipStream_t, void *, void *, int, int, int, const float2 *);
 
 static bool force_simple() {
   static const bool v = [] { const char *e = getenv("PVF_FORCE_SIMPLE"); return e && e[0] == '1'; }();
@@ -60,10 +89,21 @@ pvf_status launch_gemm(pvf_ctx *ctx, hipStream_t s, int dtype, GemmEpilogue epi,
   return launch_gemm_simple(ctx, s, dtype, epi, A, W, C, residual, M, N, K);
 }
 
-pvf_status launch_attention(pvf_ctx *ctx, hipStream_t s, int dtype, const void *qkv, void *out,
-                            int S, int T, int n_heads, int d_head) {
-  if (!force_simple() && attention_mfma_supported(dtype, T, d_head))
-    return launch_attention_mfma(ctx, s, qkv, out, S, T, n_heads, d_head);
+static bool use_attention_mfma(int dtype, int T, int d_head) {
+  return !force_simple() && attention_mfma_supported(dtype, T, d_head);
+}
+
+// Rotary embedding of q, k (in place) followed by attention.  vt: scratch of S*T*d elements,
+// needed only by the MFMA path (key-contiguous copy of v).
+static pvf_status launch_rope_attention(pvf_ctx *ctx, hipStream_t s, int dtype, void *qkv, void *vt,
+                                        void *out, int S, int T, int n_heads, int d_head,
+                                        const float2 *cos_sin) {
+  pvf_status st;
+  if (use_attention_mfma(dtype, T, d_head)) {
+    if ((st = launch_rope_vt(ctx, s, qkv, vt, S, T, n_heads, cos_sin)) != PVF_OK) return st;
+    return launch_attention_mfma(ctx, s, qkv, vt, out, S, T, n_heads);
+  }
+  if ((st = launch_rope(ctx, s, dtype, qkv, S * T, T, n_heads, d_head, cos_sin)) != PVF_OK) return st;
   return launch_attention_simple(ctx, s, dtype, qkv, out, S, T, n_heads, d_head);
 }
 
@@ -105,7 +145,9 @@ using namespace pvf;
 // context
 // =========================================================================================
 static void free_ws(pvf_ctx *c) {
-  void *ptrs[] = {c->h, c->xn, c->qkv, c->att, c->act, c->hrows, c->logits, c->seq_slot, c->row_pos, c->cos_sin};
+  for (hipEvent_t e : c->ev_pool) (void)hipEventDestroy(e);
+  c->ev_pool.clear();
+  void *ptrs[] = {c->h, c->xn, c->qkv, c->att, c->act, c->vt, c->hrows, c->logits, c->seq_slot, c->row_pos, c->cos_sin};
   for (void *p : ptrs) if (p) (void)hipFree(p);
   if (c->status_host) (void)hipHostFree(c->status_host);
 }
@@ -150,6 +192,7 @@ extern "C" pvf_status pvf_create(pvf_ctx **out, const pvf_model_cfg *m, const pv
   struct { void **p; int64_t bytes; } req[] = {
       {&c->h, M * d * (int64_t)c->esize},       {&c->xn, M * d * (int64_t)c->esize},
       {&c->qkv, M * 3 * d * (int64_t)c->esize}, {&c->att, M * d * (int64_t)c->esize},
+      {&c->vt, M * d * (int64_t)c->esize},
       {&c->act, M * ff * (int64_t)c->esize},    {&c->hrows, rows * d * (int64_t)c->esize},
       {&c->logits, rows * (int64_t)m->vocab * (int64_t)c->esize},
       {(void **)&c->seq_slot, (int64_t)max_seqs * 4}, {(void **)&c->row_pos, rows * 4},
@@ -208,20 +251,28 @@ static pvf_status forward_impl(pvf_ctx *c, hipStream_t s, const int32_t *tokens,
   const int M = S * T;
   pvf_status st;
 #define RUN(x) do { st = (x); if (st != PVF_OK) return st; } while (0)
+#define RUN_GEMM(epi, A, W, C, res, Mm, Nn, Kk)                                                   \
+  do {                                                                                            \
+    ProfScope ps(c, s, PVF_PROF_GEMM, 2.0 * (Mm) * (double)(Nn) * (Kk) * ((epi) == kEpiSwiglu ? 2 : 1), 0.0); \
+    RUN(launch_gemm(c, s, dt, epi, A, W, C, res, Mm, Nn, Kk));                                    \
+  } while (0)
   RUN(launch_embed(c, s, dt, c->w.embed, tokens, seq_slot, S, T, d, m.vocab, c->h));
   for (int l = 0; l < m.n_layers; ++l) {
     RUN(launch_rmsnorm(c, s, dt, c->h, c->attn_norm[l], c->xn, M, d, m.rms_eps));
-    RUN(launch_gemm(c, s, dt, kEpiStore, c->xn, c->wqkv[l], c->qkv, nullptr, M, 3 * d, d));
-    RUN(launch_rope(c, s, dt, c->qkv, M, T, H, dh, c->cos_sin));
-    RUN(launch_attention(c, s, dt, c->qkv, c->att, S, T, H, dh));
-    RUN(launch_gemm(c, s, dt, kEpiResidual, c->att, c->wo[l], c->h, c->h, M, d, d));
+    RUN_GEMM(kEpiStore, c->xn, c->wqkv[l], c->qkv, nullptr, M, 3 * d, d);
+    {
+      ProfScope ps(c, s, PVF_PROF_ATTENTION, 4.0 * S * (double)T * T * d, 0.0);
+      RUN(launch_rope_attention(c, s, dt, c->qkv, c->vt, c->att, S, T, H, dh, c->cos_sin));
+    }
+    RUN_GEMM(kEpiResidual, c->att, c->wo[l], c->h, c->h, M, d, d);
     RUN(launch_rmsnorm(c, s, dt, c->h, c->ffn_norm[l], c->xn, M, d, m.rms_eps));
-    RUN(launch_gemm(c, s, dt, kEpiSwiglu, c->xn, c->w_gate_up[l], c->act, nullptr, M, ff, d));
-    RUN(launch_gemm(c, s, dt, kEpiResidual, c->act, c->w_down[l], c->h, c->h, M, d, ff));
+    RUN_GEMM(kEpiSwiglu, c->xn, c->w_gate_up[l], c->act, nullptr, M, ff, d);
+    RUN_GEMM(kEpiResidual, c->act, c->w_down[l], c->h, c->h, M, d, ff);
   }
   RUN(launch_gather_rows(c, s, dt, c->h, row_pos, S, T, R, d, c->hrows));
   RUN(launch_rmsnorm(c, s, dt, c->hrows, c->w.final_norm, c->hrows, S * R, d, m.rms_eps));
-  RUN(launch_gemm(c, s, dt, kEpiStore, c->hrows, c->w.out_head, logits, nullptr, S * R, m.vocab, d));
+  RUN_GEMM(kEpiStore, c->hrows, c->w.out_head, logits, nullptr, S * R, m.vocab, d);
+#undef RUN_GEMM
 #undef RUN
   return PVF_OK;
 }
@@ -306,8 +357,11 @@ static pvf_status round_impl(pvf_ctx *ctx, hipStream_t s, int G, const uint32_t 
   st = forward_impl(ctx, s, state.canvas, ctx->seq_slot, n_seq, T, ctx->row_pos, R, ctx->logits);
   if (st != PVF_OK) return st;
   const RowFilter rf = make_filter(cfg, state, ctx->seq_slot);
-  st = launch_stage1(ctx, s, ctx->logits, ctx->model.dtype, (int64_t)n_seq * R, ctx->model.vocab,
-                     ctx->model.mask_id, cfg.logit_scale, rf, state.conf, state.tok);
+  {
+    ProfScope ps(ctx, s, PVF_PROF_STAGE1, 0.0, (double)n_seq * R * ctx->model.vocab * (double)ctx->esize);
+    st = launch_stage1(ctx, s, ctx->logits, ctx->model.dtype, (int64_t)n_seq * R, ctx->model.vocab,
+                       ctx->model.mask_id, cfg.logit_scale, rf, state.conf, state.tok);
+  }
   if (st != PVF_OK) return st;
   return launch_stage2(ctx, s, G, ctx->model.vocab, ctx->model.mask_id, plan_bitmap, cfg, state);
 }
@@ -375,6 +429,33 @@ extern "C" pvf_status pvf_decode(pvf_ctx *ctx, void *stream, const int32_t *prom
 }
 
 // =========================================================================================
+// per-kernel timing
+// =========================================================================================
+extern "C" pvf_status pvf_profile_begin(pvf_ctx *ctx) {
+  PVF_REQUIRE(nullptr, ctx != nullptr, PVF_EINVAL, "pvf_profile_begin: ctx is NULL");
+  ctx->prof.clear();
+  ctx->ev_used = 0;
+  ctx->prof_on = true;
+  return PVF_OK;
+}
+
+extern "C" pvf_status pvf_profile_end(pvf_ctx *ctx, void *stream, pvf_profile *out) {
+  PVF_REQUIRE(nullptr, ctx != nullptr, PVF_EINVAL, "pvf_profile_end: ctx is NULL");
+  PVF_REQUIRE(ctx, out != nullptr, PVF_EINVAL, "pvf_profile_end: out is NULL");
+  ctx->prof_on = false;
+  PVF_HIP_CHECK(ctx, hipStreamSynchronize((hipStream_t)stream));
+  memset(out, 0, sizeof(*out));
+  for (const auto &r : ctx->prof) {
+    float ms = 0.f;
+    PVF_HIP_CHECK(ctx, hipEventElapsedTime(&ms, r.e0, r.e1));
+    out->ms[r.cat] += ms; out->flops[r.cat] += r.flops; out->bytes[r.cat] += r.bytes; out->launches[r.cat] += 1;
+  }
+  ctx->prof.clear();
+  ctx->ev_used = 0;
+  return PVF_OK;
+}
+
+// =========================================================================================
 // building blocks
 // =========================================================================================
 static pvf_status check_dtype(int dtype) {
@@ -420,14 +501,19 @@ extern "C" pvf_status pvf_rope_attention(void *stream, int32_t dtype, void *qkv,
       tab[(size_t)t * half + i] = make_float2((float)std::cos(t * inv), (float)std::sin(t * inv));
   }
   float2 *dev = nullptr;
+  void *vt = nullptr;
   PVF_HIP_CHECK(nullptr, hipMalloc((void **)&dev, tab.size() * sizeof(float2)));
   hipError_t e = hipMemcpy(dev, tab.data(), tab.size() * sizeof(float2), hipMemcpyHostToDevice);
   pvf_status st = PVF_OK;
   if (e != hipSuccess) { set_error(nullptr, "rotary table upload: %s", hipGetErrorString(e)); st = PVF_EHIP; }
-  if (st == PVF_OK) st = launch_rope(nullptr, s, dtype, qkv, S * T, T, n_heads, d_head, dev);
-  if (st == PVF_OK) st = launch_attention(nullptr, s, dtype, qkv, out, S, T, n_heads, d_head);
+  if (st == PVF_OK && use_attention_mfma(dtype, T, d_head)) {
+    e = hipMalloc(&vt, (size_t)S * T * n_heads * d_head * 2);
+    if (e != hipSuccess) { set_error(nullptr, "scratch allocation: %s", hipGetErrorString(e)); st = PVF_EHIP; }
+  }
+  if (st == PVF_OK) st = launch_rope_attention(nullptr, s, dtype, qkv, vt, out, S, T, n_heads, d_head, dev);
   (void)hipStreamSynchronize(s);
   (void)hipFree(dev);
+  if (vt) (void)hipFree(vt);
   return st;
 }
 

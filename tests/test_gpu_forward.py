@@ -74,7 +74,9 @@ def test_rmsnorm(M, d, dtype):
 
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
 @pytest.mark.parametrize("S_,T,H,dh,theta", [(2, 128, 4, 64, 1e4), (1, 37, 2, 32, 1e4), (2, 200, 2, 128, 5e5),
-                                             (1, 512, 2, 128, 5e5), (3, 1, 1, 16, 1e4)])
+                                             (1, 512, 2, 128, 5e5), (3, 1, 1, 16, 1e4),
+                                             (2, 64, 1, 128, 5e5), (1, 192, 3, 128, 1e4),
+                                             (1, 1280, 1, 128, 5e5)])
 def test_rope_attention(S_, T, H, dh, theta, dtype):
     rng = np.random.default_rng(T + dh)
     d = H * dh
