@@ -96,13 +96,16 @@ def epilogue_roofline(B, torch, iters=24):
         B.stage1(b, mask_id, 1.0, conf, tok)
     torch.cuda.synchronize()
     us = []
-    for it in range(iters):
+    for it in range(iters // 4):
+        # four back-to-back launches (one per buffer) between a pair of events on the launch stream,
+        # so that the host's submission latency is not charged to the kernel
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
-        B.stage1(bufs[it % 4], mask_id, 1.0, conf, tok)       # launched on torch's current stream
+        for b in bufs:
+            B.stage1(b, mask_id, 1.0, conf, tok)              # launched on torch's current stream
         e1.record()
         torch.cuda.synchronize()
-        us.append(e0.elapsed_time(e1) * 1e3)
+        us.append(e0.elapsed_time(e1) * 1e3 / len(bufs))
     us = np.array(us)
     algo = rows * V * 2 + rows * 8
     ach = algo / (us.mean() * 1e-6) / 1e9
