@@ -44,6 +44,9 @@ def parse():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-epilogue", action="store_true")
+    ap.add_argument("--pmc-reference", action="store_true",
+                    help="also run a plain device-to-device copy of 256 MiB (reference for scaling "
+                         "rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
     return ap.parse_args()
 
 
@@ -196,6 +199,8 @@ def main():
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(gemm_tflops / PEAK_BF16_TFLOPS, 4),
                      "traffic": TRAFFIC_GEMM, "launches": int(g["launches"]),
                      "avg_launch_us": round(g["ms"] * 1e3 / max(1, g["launches"]), 2),
+                     "algorithmic_flops_per_launch": round(g["flops"] / max(1, g["launches"])),
+                     "algorithmic_bytes_per_launch": round(g["bytes"] / max(1, g["launches"])),
                      "gemm_share_of_step_time": round(g["ms"] * 1e-3 / dt, 4),
                      "attention_tflops": round(prof["attention"]["flops"] / max(prof["attention"]["ms"], 1e-9) / 1e9, 1),
                      "stage1_gbs_in_round": round(prof["stage1"]["bytes"] / max(prof["stage1"]["ms"], 1e-9) / 1e6, 1)},
@@ -220,6 +225,13 @@ def main():
         except Exception:
             threads = os.cpu_count() or 1
         res["cpu_baseline"] = cpu_baseline(dims, T, R, seqs / a.steps, tpf, threads)
+    if a.pmc_reference:
+        src = torch.empty(256 * 1024 * 1024 // 2, dtype=torch.bfloat16, device="cuda")
+        B.fill_normal(src, 99, 0.0, 1.0)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
     print(json.dumps(res))
 
 

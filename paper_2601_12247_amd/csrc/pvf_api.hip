@@ -253,7 +253,9 @@ static pvf_status forward_impl(pvf_ctx *c, hipStream_t s, const int32_t *tokens,
 #define RUN(x) do { st = (x); if (st != PVF_OK) return st; } while (0)
 #define RUN_GEMM(epi, A, W, C, res, Mm, Nn, Kk)                                                   \
   do {                                                                                            \
-    ProfScope ps(c, s, PVF_PROF_GEMM, 2.0 * (Mm) * (double)(Nn) * (Kk) * ((epi) == kEpiSwiglu ? 2 : 1), 0.0); \
+    ProfScope ps(c, s, PVF_PROF_GEMM, 2.0 * (Mm) * (double)(Nn) * (Kk) * ((epi) == kEpiSwiglu ? 2 : 1),   \
+                 (double)c->esize * ((double)(Mm) * (Kk) + (double)(Nn) * (Kk) * ((epi) == kEpiSwiglu ? 2 : 1) + \
+                                     (double)(Mm) * (Nn) * ((epi) == kEpiResidual ? 2 : 1)));             \
     RUN(launch_gemm(c, s, dt, epi, A, W, C, res, Mm, Nn, Kk));                                    \
   } while (0)
   RUN(launch_embed(c, s, dt, c->w.embed, tokens, seq_slot, S, T, d, m.vocab, c->h));
