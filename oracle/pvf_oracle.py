@@ -38,6 +38,10 @@ Readings taken where the paper is silent (all listed again in the design notes):
   R9  after a planning round in which every draft is rejected, only the base
       branch is committed (no AR attempt in the same round).
   R10 blocks tile the generation region only; gen_len % block_len == 0.
+  R11 early cross-block revelation (App. A.4.1, Eq. block_expansion): the working set of a step
+      is fixed when the step's proposal is made, from the canvas before the base commits; the
+      same set is used for the base commit, the candidates, the impact set and C_total of that
+      step.  "Active block" everywhere above means this working set.
 
 Parity status: every function below is pinned by tests/test_oracle_*.py
 (closed forms, library special cases, invariants, brute force).  Absolute
@@ -87,6 +91,7 @@ class DecodeCfg:
     tau_ar_lo: float = 0.1
     K: int = 3
     routes: int = ROUTES_BIT_PLAN | ROUTES_BIT_AR
+    n_sparse: int = 0      # N_s of Eq. (block_expansion); 0 = early cross-block revelation off
 
     @property
     def T(self) -> int:
@@ -98,12 +103,14 @@ class DecodeCfg:
 
     @property
     def window_rows(self) -> int:
-        """Rows scored per canvas: the active block and the one after it."""
-        return min(2 * self.block_len, self.gen_len)
+        """Rows scored per canvas, starting at the active block k.  Without early revelation the
+        next working block is k or k+1 (2 blocks of rows); with it the working set of this round
+        can be {k, k+1} and the next one {k+2, k+3} (4 blocks of rows)."""
+        return min((4 if self.n_sparse > 0 else 2) * self.block_len, self.gen_len)
 
     def check(self) -> None:
         assert self.block_len > 0 and self.gen_len % self.block_len == 0
-        assert self.K >= 0 and self.prompt_len >= 0
+        assert self.K >= 0 and self.prompt_len >= 0 and self.n_sparse >= 0
         assert self.tau_plan_lo <= self.tau_plan_hi <= self.tau_high
 
 
@@ -222,6 +229,7 @@ class State:
     drafts: Drafts
     k_active: int = 0
     done: bool = False
+    ws: int = 1                      # blocks in the working set B_t this batch was formed on (1 or 2)
 
 
 @dataclass
@@ -267,6 +275,15 @@ def first_masked_block(y: np.ndarray, cfg: DecodeCfg, mask_id: int) -> int:
     return -1
 
 
+def working_blocks(y: np.ndarray, k: int, cfg: DecodeCfg, mask_id: int) -> int:
+    """Eq. (block_expansion): the working set is the active block k, plus the whole next block
+    when at most N_s masks are left in block k (and a next block exists).  Returns 1 or 2."""
+    if cfg.n_sparse <= 0 or k + 1 >= cfg.n_blocks:
+        return 1
+    lo = cfg.prompt_len + k * cfg.block_len
+    return 2 if int(np.sum(y[lo: lo + cfg.block_len] == mask_id)) <= cfg.n_sparse else 1
+
+
 def window_positions(cfg: DecodeCfg, k_active: int) -> np.ndarray:
     """Canvas positions of the R scored rows; entries >= T mark rows that do not exist."""
     return cfg.prompt_len + k_active * cfg.block_len + np.arange(cfg.window_rows)
@@ -283,7 +300,7 @@ def decide(state: State, conf: np.ndarray, tok: np.ndarray, cfg: DecodeCfg,
     bl = cfg.block_len
     X = branch_canvases(state.y, state.drafts)
     w0 = cfg.prompt_len + state.k_active * bl              # canvas position of window row 0
-    B = list(range(w0, w0 + bl))                           # active block
+    B = list(range(w0, w0 + state.ws * bl))                # working set this batch was formed on
     dr = state.drafts
     info = RoundInfo(accept=[0] * dr.n, winner=0, route=dr.route if dr.n else ROUTE_NONE)
 
@@ -325,12 +342,13 @@ def decide(state: State, conf: np.ndarray, tok: np.ndarray, cfg: DecodeCfg,
     k_new = first_masked_block(y, cfg, mask_id)
     if k_new < 0:
         return State(y, Drafts(), state.k_active, True), info
-    assert k_new in (state.k_active, state.k_active + 1)
+    assert state.k_active <= k_new <= state.k_active + state.ws
 
     # ---- propose from the winner's own predictions ----------------------------
     cw, tw = conf[info.winner], tok[info.winner]
     b0 = cfg.prompt_len + k_new * bl
-    M = [i for i in range(b0, b0 + bl) if y[i] == mask_id]
+    ws_new = working_blocks(y, k_new, cfg, mask_id)         # decided on y_t, before the base commits
+    M = [i for i in range(b0, b0 + ws_new * bl) if y[i] == mask_id]
     for i in M:
         _margin_cmp(info, cw[i - w0], f32(cfg.tau_high))
     S_base = [i for i in M if f32(cw[i - w0]) >= f32(cfg.tau_high)]
@@ -347,7 +365,7 @@ def decide(state: State, conf: np.ndarray, tok: np.ndarray, cfg: DecodeCfg,
         y[i] = tw[i - w0]
     info.n_base = len(S_base)
     if first_masked_block(y, cfg, mask_id) < 0:
-        return State(y, Drafts(), k_new, True), info       # nothing left: no further forward
+        return State(y, Drafts(), k_new, True, ws_new), info   # nothing left: no further forward
 
     Rm = [i for i in M if i not in S_base]
     nxt = Drafts()
@@ -374,7 +392,7 @@ def decide(state: State, conf: np.ndarray, tok: np.ndarray, cfg: DecodeCfg,
                 cand.append(i)
         if cand:
             nxt = Drafts(ROUTE_AR, [(i, int(tw[i - w0])) for i in sorted(cand)[: cfg.K]])
-    return State(y, nxt, k_new, False), info
+    return State(y, nxt, k_new, False, ws_new), info
 
 
 # =============================================================================
@@ -459,7 +477,7 @@ def decode_literal(prompt: Sequence[int], forward_fn: ForwardFn, cfg: DecodeCfg,
     while np.any(y == mask_id):
         k = first_masked_block(y, cfg, mask_id)
         b0 = cfg.prompt_len + k * cfg.block_len
-        B = list(range(b0, b0 + cfg.block_len))
+        B = list(range(b0, b0 + working_blocks(y, k, cfg, mask_id) * cfg.block_len))
         p, yh = stage1(forward_fn(y)[B], scale, mask_id); nfe += 1
         M = [i for i in B if y[i] == mask_id]
         S_base = [i for i in M if f32(p[i - b0]) >= f32(cfg.tau_high)]
