@@ -26,10 +26,13 @@
  *     logits; accumulation is always float32).
  *   - Canvas positions: [0, prompt_len) prompt, then gen_len generated tokens split into
  *     gen_len / block_len blocks (App. A.1).  T = prompt_len + gen_len.
- *   - Window: the R = min(2*block_len, gen_len) canvas positions starting at the first
- *     position of the active block; row r of a canvas is position
- *     prompt_len + k_active*block_len + r.  Rows whose position is >= T do not exist:
- *     their summaries are conf = 0, tok = -1.
+ *   - Window: the R = min(c*block_len, gen_len) canvas positions starting at the first
+ *     position of the active block, c = 2 (c = 4 when n_sparse > 0); row r of a canvas is
+ *     position prompt_len + k_active*block_len + r.  Rows whose position is >= T do not
+ *     exist: their summaries are conf = 0, tok = -1.
+ *   - Working set B_t: the active block; with n_sparse = N_s > 0 also the whole next block
+ *     once the active block holds at most N_s masks (App. A.4.1, Eq. block_expansion).
+ *     Impact set, compatibility, C_total, commits and candidates all range over B_t.
  */
 #ifndef PVF_H
 #define PVF_H
@@ -78,7 +81,8 @@ typedef struct {
   int32_t prompt_len;
   int32_t gen_len;
   int32_t routes;       /* bit 0 planning route, bit 1 AR route; 0 = threshold decoding */
-  int32_t n_sparse;     /* early cross-block revelation threshold N_s; must be 0       */
+  int32_t n_sparse;     /* early cross-block revelation threshold N_s (App. A.4.1);     */
+                        /* 0 = off: the working set is always the active block alone   */
 } pvf_decode_cfg;
 
 #define PVF_MAX_K 16
@@ -106,6 +110,8 @@ typedef struct {
                         /*              = backbone + fill j; AR draft k = backbone +      */
                         /*              fills 1..k                                        */
   int32_t *k_active;    /* [G]          index of the active block (in/out)                */
+  int32_t *n_ws_blocks; /* [G]          blocks in the working set the batch was formed on: */
+                        /*              1, or 2 after early cross-block revelation (in/out) */
   float   *conf;        /* [G, 1+K, R]  out: top-1 probability per window row             */
   int32_t *tok;         /* [G, 1+K, R]  out: top-1 token per window row                   */
   uint8_t *accept;      /* [G, K]       out: A_j (planning) / pass bit (AR) of THIS batch */
@@ -175,7 +181,7 @@ pvf_status pvf_epilogue(pvf_ctx *ctx, void *stream, const void *logits, int32_t 
 pvf_status pvf_round(pvf_ctx *ctx, void *stream, int32_t G, const uint32_t *plan_bitmap,
                      const pvf_decode_cfg *cfg, const pvf_state *state, int32_t n_seq_host);
 
-/* y_0 = [prompt | MASK^gen_len] in every slot, no drafts, k_active = 0, done = 0.
+/* y_0 = [prompt | MASK^gen_len] in every slot, no drafts, k_active = 0, n_ws_blocks = 1, done = 0.
  *   prompt dev int32 [G, prompt_len]; must not contain mask_id (not checked on device). */
 pvf_status pvf_state_init(pvf_ctx *ctx, void *stream, const int32_t *prompt, int32_t G,
                           const pvf_decode_cfg *cfg, const pvf_state *state);

@@ -57,7 +57,8 @@ class WeightsC(C.Structure):
 
 class StateC(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in
-                ("canvas", "n_drafts", "draft_route", "fill_pos", "fill_tok", "k_active", "conf",
+                ("canvas", "n_drafts", "draft_route", "fill_pos", "fill_tok", "k_active", "n_ws_blocks",
+                 "conf",
                  "tok", "accept", "winner", "n_commit", "done")]
 
 
@@ -168,7 +169,7 @@ class DecodeCfg:
 
     @property
     def R(self) -> int:
-        return min(2 * self.block_len, self.gen_len)
+        return min((4 if self.n_sparse > 0 else 2) * self.block_len, self.gen_len)
 
     def c(self) -> DecodeCfgC:
         return DecodeCfgC(self.tau_high, self.tau_plan_lo, self.tau_plan_hi, self.tau_ar_lo,
@@ -189,6 +190,7 @@ class State:
         self.fill_pos = torch.full((G, max(K, 1)), -1, **i32)
         self.fill_tok = torch.full((G, max(K, 1)), -1, **i32)
         self.k_active = torch.zeros(G, **i32)
+        self.n_ws_blocks = torch.ones(G, **i32)
         self.conf = torch.zeros(G, 1 + K, R, dtype=torch.float32, device=device)
         self.tok = torch.zeros(G, 1 + K, R, **i32)
         self.accept = torch.zeros(G, max(K, 1), dtype=torch.uint8, device=device)

@@ -15,6 +15,7 @@ LIB = os.path.join(HERE, "libpvf.so")
 SOURCES = [
     "pvf_api.hip",
     "epilogue.hip",
+    "decision.hip",
     "elementwise.hip",
     "gemm_simple.hip",
     "gemm_mfma.hip",

@@ -72,6 +72,9 @@ pvf_status launch_stage1(pvf_ctx *ctx, hipStream_t s, const void *logits, int dt
                          int64_t n_rows, int vocab, int mask_id, float scale,
                          const RowFilter &rf, float *conf, int32_t *tok);
 
+// rows of the decision window: min(c * block_len, gen_len), c = 2, or 4 with n_sparse > 0
+int window_rows(const pvf_decode_cfg &c);
+
 pvf_status launch_stage2(pvf_ctx *ctx, hipStream_t s, int G, int vocab, int mask_id,
                          const uint32_t *plan_bitmap, const pvf_decode_cfg &cfg,
                          const pvf_state &st);

@@ -108,10 +108,6 @@ static pvf_status launch_rope_attention(pvf_ctx *ctx, hipStream_t s, int dtype, 
 }
 
 // ---- validation -----------------------------------------------------------------------
-static int window_rows(const pvf_decode_cfg &c) {
-  return (2 * c.block_len < c.gen_len) ? 2 * c.block_len : c.gen_len;
-}
-
 static pvf_status check_decode_cfg(pvf_ctx *ctx, const pvf_decode_cfg *c, int vocab, int mask_id) {
   PVF_REQUIRE(ctx, c != nullptr, PVF_EINVAL, "decode cfg is NULL");
   PVF_REQUIRE(ctx, c->K >= 0 && c->K <= PVF_MAX_K, PVF_EINVAL, "K=%d outside [0,%d]", c->K, PVF_MAX_K);
@@ -122,7 +118,7 @@ static pvf_status check_decode_cfg(pvf_ctx *ctx, const pvf_decode_cfg *c, int vo
               "need tau_plan_lo <= tau_plan_hi <= tau_high (%g, %g, %g)", c->tau_plan_lo, c->tau_plan_hi, c->tau_high);
   PVF_REQUIRE(ctx, c->logit_scale > 0.f && std::isfinite(c->logit_scale), PVF_EINVAL, "logit_scale=%g must be positive", c->logit_scale);
   PVF_REQUIRE(ctx, (c->routes & ~3) == 0, PVF_EINVAL, "routes=%d has unknown bits", c->routes);
-  PVF_REQUIRE(ctx, c->n_sparse == 0, PVF_ENOTIMPL, "n_sparse=%d: early cross-block revelation is not built", c->n_sparse);
+  PVF_REQUIRE(ctx, c->n_sparse >= 0, PVF_EINVAL, "n_sparse=%d must be >= 0", c->n_sparse);
   PVF_REQUIRE(ctx, mask_id >= 0 && mask_id < vocab, PVF_EINVAL, "mask_id=%d outside [0,%d)", mask_id, vocab);
   PVF_REQUIRE(ctx, (int64_t)(1 + c->K) * window_rows(*c) <= PVF_MAX_SUMMARIES, PVF_ESHAPE,
               "(1+K)*R = %lld exceeds %d", (long long)(1 + c->K) * window_rows(*c), PVF_MAX_SUMMARIES);
@@ -132,7 +128,7 @@ static pvf_status check_decode_cfg(pvf_ctx *ctx, const pvf_decode_cfg *c, int vo
 static pvf_status check_state(pvf_ctx *ctx, const pvf_state *st) {
   PVF_REQUIRE(ctx, st != nullptr, PVF_EINVAL, "state is NULL");
   PVF_REQUIRE(ctx, st->canvas && st->n_drafts && st->draft_route && st->fill_pos && st->fill_tok &&
-                  st->k_active && st->conf && st->tok && st->accept && st->winner && st->n_commit && st->done,
+                  st->k_active && st->n_ws_blocks && st->conf && st->tok && st->accept && st->winner && st->n_commit && st->done,
               PVF_EINVAL, "state has a NULL member");
   return PVF_OK;
 }

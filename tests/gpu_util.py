@@ -19,7 +19,7 @@ def oracle_model_cfg(shape: S.ModelShape, n_layers=None) -> O.ModelCfg:
 def oracle_decode_cfg(c: B.DecodeCfg) -> O.DecodeCfg:
     return O.DecodeCfg(block_len=c.block_len, prompt_len=c.prompt_len, gen_len=c.gen_len,
                        tau_high=c.tau_high, tau_plan_lo=c.tau_plan_lo, tau_plan_hi=c.tau_plan_hi,
-                       tau_ar_lo=c.tau_ar_lo, K=c.K, routes=c.routes)
+                       tau_ar_lo=c.tau_ar_lo, K=c.K, routes=c.routes, n_sparse=c.n_sparse)
 
 
 def to_device(w, dtype=torch.float32, device="cuda"):
@@ -43,7 +43,8 @@ def oracle_state(st: B.State, g: int) -> O.State:
     fp, ft = st.fill_pos[g].cpu().numpy(), st.fill_tok[g].cpu().numpy()
     fills = [(int(fp[j]), int(ft[j])) for j in range(n)]
     return O.State(st.canvas[g, 0].cpu().numpy().astype(np.int32).copy(),
-                   O.Drafts(route, fills), int(st.k_active[g]), bool(st.done[g]))
+                   O.Drafts(route, fills), int(st.k_active[g]), bool(st.done[g]),
+                   ws=int(st.n_ws_blocks[g]))
 
 
 def assert_state_equals(st: B.State, g: int, want: O.State, info: O.RoundInfo, cfg: B.DecodeCfg,
@@ -59,6 +60,7 @@ def assert_state_equals(st: B.State, g: int, want: O.State, info: O.RoundInfo, c
     assert int(st.n_drafts[g]) == want.drafts.n, f"{where}: number of drafts"
     if not want.done:
         assert int(st.k_active[g]) == want.k_active, f"{where}: active block"
+        assert int(st.n_ws_blocks[g]) == want.ws, f"{where}: working-set blocks"
     if want.drafts.n:
         assert int(st.draft_route[g]) == want.drafts.route, f"{where}: route"
         fp, ft = st.fill_pos[g].cpu().numpy(), st.fill_tok[g].cpu().numpy()

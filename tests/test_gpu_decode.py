@@ -57,7 +57,7 @@ def find_case(shape, fwd, cfg, G, first_seed, plan_n=64):
     pytest.fail(f"no seed with decision margin >= {MARGIN}")
 
 
-def step_and_compare(shape, ctx, fwd, cfg, prompts, plan, compact):
+def step_and_compare(shape, ctx, fwd, cfg, prompts, plan, compact, ws_trace=None):
     """Drive pvf_round from Python and compare the state with the oracle after every round."""
     G = len(prompts)
     ocfg = oracle_decode_cfg(cfg)
@@ -79,6 +79,8 @@ def step_and_compare(shape, ctx, fwd, cfg, prompts, plan, compact):
                 continue
             new, info = O.pvf_round(ost[g], fwd, ocfg, cfg.logit_scale, shape.mask_id, plan)
             assert_state_equals(st, g, new, info, cfg, where=f"round {rounds} group {g}")
+            if ws_trace is not None:
+                ws_trace.append((new.ws, ost[g].ws, sum(info.accept)))
             ost[g] = new
         assert rounds <= cfg.gen_len + 1
     return st, rounds
@@ -141,6 +143,46 @@ def test_threshold_mode_and_single_routes(tiny, kw):
     assert stats.n_plan == sum(r.n_plan for r in res) and stats.n_ar == sum(r.n_ar for r in res)
     if kw.get("K") == 0 or kw.get("routes") == 0:
         assert stats.n_plan == 0 and stats.n_ar == 0 and stats.seq_forwards == sum(r.nfe for r in res)
+
+
+@pytest.mark.parametrize("n_sparse", [4, 16])
+def test_early_cross_block_revelation_end_to_end(tiny, n_sparse):
+    """N_s > 0 (App. A.4.1): every round and the committed sequence match the oracle."""
+    shape, ctx, fwd = tiny
+    cfg = B.DecodeCfg(block_len=16, prompt_len=32, gen_len=64, K=3, tau_high=0.9, tau_ar_lo=0.3,
+                      logit_scale=shape.logit_scale, n_sparse=n_sparse)
+    assert cfg.R == 64
+    seed, prompts, plan, res = find_case(shape, fwd, cfg, 2, first_seed=120, plan_n=400)
+    trace = []
+    st, rounds = step_and_compare(shape, ctx, fwd, cfg, prompts, plan, compact=True, ws_trace=trace)
+    assert rounds == max(r.nfe for r in res)
+    assert any(w == 2 for w, _, _ in trace)            # the working set did widen
+    for g in range(2):
+        assert np.array_equal(st.canvas[g, 0].cpu().numpy(), res[g].tokens)
+    bitmap = dev(S.plan_bitmap(plan, shape.vocab).view(np.int32), torch.int32)
+    out, stats = ctx.decode(B.State(2, cfg), dev(np.stack(prompts), torch.int32), bitmap)
+    for g in range(2):
+        assert np.array_equal(out[g].cpu().numpy(), res[g].tokens)
+    assert stats.rounds == max(r.nfe for r in res)
+    assert (stats.n_base, stats.n_plan, stats.n_ar) == tuple(sum(getattr(r, k) for r in res)
+                                                             for k in ("n_base", "n_plan", "n_ar"))
+
+
+def test_static_decoding_and_full_expansion_round_counts(tiny):
+    """tau_high above 1 never fires, so the progress rule commits one token per forward
+    (static one-token-per-step decoding); tau_high = 0 with N_s = block length commits two
+    blocks per forward."""
+    shape, ctx, fwd = tiny
+    prompts = [S.make_prompt(5, 16, shape.vocab, shape.mask_id)]
+    bitmap = torch.zeros((shape.vocab + 31) // 32, dtype=torch.int32, device="cuda")
+    cfg = B.DecodeCfg(block_len=16, prompt_len=16, gen_len=32, K=0, tau_high=1.5, tau_plan_lo=0.0,
+                      tau_plan_hi=0.0, logit_scale=shape.logit_scale)
+    out, stats = ctx.decode(B.State(1, cfg), dev(np.stack(prompts), torch.int32), bitmap)
+    assert stats.rounds == 32 and stats.n_base == 32 and not (out == shape.mask_id).any()
+    cfg = B.DecodeCfg(block_len=16, prompt_len=16, gen_len=64, K=2, tau_high=0.0, tau_plan_lo=0.0,
+                      tau_plan_hi=0.0, logit_scale=shape.logit_scale, n_sparse=16)
+    out, stats = ctx.decode(B.State(1, cfg), dev(np.stack(prompts), torch.int32), bitmap)
+    assert stats.rounds == 2 and stats.n_base == 64 and not (out == shape.mask_id).any()
 
 
 def test_tau_high_zero_needs_one_round_per_block(tiny):

@@ -96,10 +96,11 @@ def draft_consistent_logits(rng, G, K, R, V, mask_id, boost_hi, jitter):
 
 
 def run_two_rounds(seed, G, K, bl, gen_len, V, dtype, routes=3, tau_high=0.9, boost_hi=18.0,
-                   plan_n=None, jitter=0.4, prompt_len=4, band=(0.2, 0.65)):
+                   plan_n=None, jitter=0.4, prompt_len=4, band=(0.2, 0.65), n_sparse=0, rounds=3):
     mask_id = V - 1
     cfg = B.DecodeCfg(block_len=bl, prompt_len=prompt_len, gen_len=gen_len, K=K, routes=routes,
-                      tau_high=tau_high, tau_plan_lo=band[0], tau_plan_hi=band[1], logit_scale=1.0)
+                      tau_high=tau_high, tau_plan_lo=band[0], tau_plan_hi=band[1], logit_scale=1.0,
+                      n_sparse=n_sparse)
     ocfg = oracle_decode_cfg(cfg)
     R = cfg.R
     rng = np.random.default_rng(seed)
@@ -112,8 +113,8 @@ def run_two_rounds(seed, G, K, bl, gen_len, V, dtype, routes=3, tau_high=0.9, bo
     st.canvas[:, :, :prompt_len] = dev(prompts, torch.int32)[:, None, :]
     ost = [O.initial_state(prompts[g], ocfg, mask_id) for g in range(G)]
     margin = np.inf
-    seen = {"accept": 0, "reject": 0, "plan": 0, "ar": 0}
-    for rnd in range(3):
+    seen = {"accept": 0, "reject": 0, "plan": 0, "ar": 0, "wide": 0, "wide_accept": 0}
+    for rnd in range(rounds):
         lg = draft_consistent_logits(rng, G, K, R, V, mask_id, boost_hi, jitter)
         B.epilogue(dev(lg, dtype), st, bitmap, V, mask_id)
         torch.cuda.synchronize()
@@ -135,6 +136,7 @@ def run_two_rounds(seed, G, K, bl, gen_len, V, dtype, routes=3, tau_high=0.9, bo
                 assert_state_equals(st, g, new, info, cfg, where=f"seed {seed} round {rnd} group {g}")
             seen["accept"] += sum(info.accept); seen["reject"] += len(info.accept) - sum(info.accept)
             seen["plan"] += info.route == 1; seen["ar"] += info.route == 2
+            seen["wide"] += new.ws == 2; seen["wide_accept"] += sum(info.accept) if ost[g].ws == 2 else 0
             ost[g] = new
         if margin < 1e-5:
             return margin, seen
@@ -157,6 +159,22 @@ def test_epilogue_rounds_match_oracle_small_vocab(dtype):
         for k in tot:
             tot[k] += seen[k]
     assert all(v > 0 for v in tot.values()), tot      # both routes, both outcomes were exercised
+
+
+@pytest.mark.parametrize("n_sparse,bl,gen_len,rounds", [(16, 16, 64, 5), (6, 16, 48, 8), (32, 32, 64, 4),
+                                                        (3, 8, 8, 4)])
+def test_epilogue_early_cross_block_revelation(n_sparse, bl, gen_len, rounds):
+    """Working sets of two blocks (App. A.4.1): verify, commit and propose all range over both."""
+    tot = {"accept": 0, "reject": 0, "wide": 0, "wide_accept": 0}
+    for first in (700, 720):
+        seed, seen = walk_seeds(first, G=4, K=4, bl=bl, gen_len=gen_len, V=2048, dtype=torch.float32,
+                                n_sparse=n_sparse, rounds=rounds, tau_high=0.85)
+        for k in tot:
+            tot[k] += seen[k]
+    if gen_len > bl:
+        assert tot["wide"] > 0 and tot["wide_accept"] > 0 and tot["reject"] > 0, tot
+    else:
+        assert tot["wide"] == 0                        # a single block has nothing to reveal
 
 
 @pytest.mark.parametrize("routes,K", [(0, 3), (1, 2), (2, 8), (3, 0), (3, 1)])
@@ -191,7 +209,7 @@ def test_epilogue_rejects_bad_configuration():
     st.cfg = B.DecodeCfg(block_len=4, prompt_len=0, gen_len=12, K=2, tau_plan_hi=0.95)  # band above tau_high
     with pytest.raises(B.PvfError):
         B.epilogue(lg, st, bm, 64, 63)
-    st.cfg = B.DecodeCfg(block_len=4, prompt_len=0, gen_len=12, K=2, n_sparse=5)
+    st.cfg = B.DecodeCfg(block_len=4, prompt_len=0, gen_len=12, K=2, n_sparse=-1)
     with pytest.raises(B.PvfError) as e:
         B.epilogue(lg, st, bm, 64, 63)
-    assert e.value.status == -5
+    assert e.value.status == -1
