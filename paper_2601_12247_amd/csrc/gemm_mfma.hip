@@ -31,7 +31,6 @@ namespace {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
-constexpr int kThreads = 256;
 constexpr int kGroupM = 8;
 
 typedef __attribute__((address_space(1))) const void gptr_t;
@@ -46,37 +45,49 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
 
 // s_waitcnt vmcnt(n) only (expcnt / lgkmcnt left at "no wait"); n is a 6-bit field split 4 + 2
 template <int N> __device__ __forceinline__ void wait_vmcnt() {
+  static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
   __builtin_amdgcn_s_waitcnt(0x0f70 | (N & 15) | ((N >> 4) << 14));
 }
 
 // Row of W that feeds row r (0..BN-1) of the workgroup's W tile.
 //  plain:   consecutive rows tile_n*BN + r.
-//  SwiGLU:  the tile covers BN/2 output columns; inside each wave's BN/2 tile rows the 32-row
+//  SwiGLU:  the tile covers BN/2 output columns; inside each wave's BN/WN tile rows the 32-row
 //           MFMA sub-tiles alternate gate / up for the same 32 columns, so silu(g)*u pairs
 //           accumulators of one lane.
-template <int EPI, int BN>
+template <int EPI, int BN, int WN>
 __device__ __forceinline__ int w_row(int r, int tile_n, int ff) {
   if (EPI != kEpiSwiglu) return tile_n * BN + r;
-  const int wn = r / (BN / 2), t = (r % (BN / 2)) >> 5, e = r & 31;
-  const int col = tile_n * (BN / 2) + wn * (BN / 4) + (t >> 1) * 32 + e;
+  constexpr int WT = BN / WN;
+  const int wn = r / WT, t = (r % WT) >> 5, e = r & 31;
+  const int col = tile_n * (BN / 2) + wn * (WT / 2) + (t >> 1) * 32 + e;
   return (t & 1) ? ff + col : col;
 }
 
-template <int EPI, int BM, int BN, int BK, int kStages>
-__global__ void __launch_bounds__(kThreads, (kStages * (BM + BN) * BK * 2 <= 80 * 1024) ? 2 : 1)
+// workgroups per CU (by LDS) x waves per workgroup / 4 SIMDs
+constexpr int waves_per_simd(int lds_bytes, int waves) { return (lds_bytes <= 80 * 1024 ? 2 : 1) * waves / 4; }
+
+template <int EPI, int BM, int BN, int BK, int kStages, int WM, int WN>
+__global__ void __launch_bounds__(64 * WM * WN)
+__attribute__((amdgpu_waves_per_eu(waves_per_simd(kStages * (BM + BN) * BK * 2, WM * WN),
+                                   waves_per_simd(kStages * (BM + BN) * BK * 2, WM * WN))))
 gemm_bf16_mfma_kernel(const bf16_t *__restrict__ A, const bf16_t *__restrict__ W,
                       bf16_t *__restrict__ C, const bf16_t *__restrict__ Res, int M, int N_out,
                       int K, int tiles_m, int tiles_n) {
-  constexpr int MT = BM / 64, NT = BN / 64;          // MFMA tiles per wave in each direction
+  constexpr int kThreads = 64 * WM * WN;
+  constexpr int MT = BM / (32 * WM), NT = BN / (32 * WN);  // MFMA tiles per wave in each direction
   constexpr int kATile = BM * BK * 2, kWTile = BN * BK * 2, kStage = kATile + kWTile;
   constexpr int CPR = BK / 8;                        // 16-byte chunks per LDS row
-  constexpr int RPI = 256 / CPR;                     // tile rows covered by one load instruction of the block
+  constexpr int RPI = kThreads / CPR;                // tile rows covered by one load instruction of the block
+  constexpr int kInstrBytes = kThreads * 16;         // LDS bytes filled by one load instruction of the block
   constexpr int LA = BM / RPI, LW = BN / RPI;        // direct loads per thread per stage
   constexpr int KS = BK / 16;                        // MFMA k-steps per stage
   constexpr int kRowBytes = BK * 2;
+  static_assert(BM % RPI == 0 && BN % RPI == 0 && KS >= 2, "tile shape");
+  static_assert(EPI != kEpiSwiglu || NT % 2 == 0, "SwiGLU pairs gate/up sub-tiles inside a wave");
   extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform: LDS targets become scalar arithmetic
+  const int wm = wave / WN, wn = wave % WN;
 
   // ---- XCD-aware tile assignment ----
   const int total = tiles_m * tiles_n;
@@ -90,37 +101,30 @@ gemm_bf16_mfma_kernel(const bf16_t *__restrict__ A, const bf16_t *__restrict__ W
   const int tile_m = band * kGroupM + (within - tile_n * band_rows);
   const int m0 = tile_m * BM;
 
-  // ---- global -> LDS: thread tid fills 16-byte slot (i*256 + tid) of an operand tile:
+  // ---- global -> LDS: thread tid fills 16-byte slot (i*kThreads + tid) of an operand tile:
   //      tile row i*RPI + tid/CPR, slot position tid%CPR, k-chunk position ^ swizzle(row) ----
   const int ld_row = tid / CPR;
   const int ld_chunk = (tid % CPR) ^ (CPR == 8 ? (ld_row >> 1) & 7 : (ld_row >> 2) & 3);
-  const bf16_t *a_src[LA], *w_src[LW];
+  // Per-lane byte offsets (32 bit) from the operand base; the k advance goes into the uniform
+  // base pointer, so a load needs no per-lane address arithmetic.
+  uint32_t a_off[LA], w_off[LW];
 #pragma unroll
   for (int i = 0; i < LA; ++i) {
     const int am = min(m0 + i * RPI + ld_row, M - 1);         // ragged last tile: re-read a valid row
-    a_src[i] = A + (int64_t)am * K + ld_chunk * 8;
+    a_off[i] = ((uint32_t)am * (uint32_t)K + ld_chunk * 8) * 2u;
   }
 #pragma unroll
   for (int i = 0; i < LW; ++i)
-    w_src[i] = W + (int64_t)w_row<EPI, BN>(i * RPI + ld_row, tile_n, N_out) * K + ld_chunk * 8;
-  auto issue_loads = [&](int kt) {
-    unsigned char *dst = lds + (kt % kStages) * kStage + wave * 1024;
-    const int koff = kt * BK;
-#pragma unroll
-    for (int i = 0; i < LA; ++i)
-      __builtin_amdgcn_global_load_lds((gptr_t *)(a_src[i] + koff), (lptr_t *)(dst + i * 4096), 16, 0, 0);
-#pragma unroll
-    for (int i = 0; i < LW; ++i)
-      __builtin_amdgcn_global_load_lds((gptr_t *)(w_src[i] + koff), (lptr_t *)(dst + kATile + i * 4096), 16, 0, 0);
-  };
+    w_off[i] = ((uint32_t)w_row<EPI, BN, WN>(i * RPI + ld_row, tile_n, N_out) * (uint32_t)K + ld_chunk * 8) * 2u;
+  const char *Ab = reinterpret_cast<const char *>(A), *Wb = reinterpret_cast<const char *>(W);
   constexpr int kLoadsPerStage = LA + LW;
   auto issue_one = [&](int kt, int i) {                      // load i (A loads first, then W) of stage kt
     unsigned char *dst = lds + (kt % kStages) * kStage + wave * 1024;
-    const int koff = kt * BK;
+    const size_t koff = (size_t)kt * (BK * 2);
     if (i < LA)
-      __builtin_amdgcn_global_load_lds((gptr_t *)(a_src[i] + koff), (lptr_t *)(dst + i * 4096), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((gptr_t *)(Ab + koff + a_off[i]), (lptr_t *)(dst + i * kInstrBytes), 16, 0, 0);
     else
-      __builtin_amdgcn_global_load_lds((gptr_t *)(w_src[i - LA] + koff), (lptr_t *)(dst + kATile + (i - LA) * 4096), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((gptr_t *)(Wb + koff + w_off[i - LA]), (lptr_t *)(dst + kATile + (i - LA) * kInstrBytes), 16, 0, 0);
   };
 
   // ---- LDS -> MFMA operands: lane reads row (base + lane%32), chunk (2*kk + lane/32) ----
@@ -129,8 +133,8 @@ gemm_bf16_mfma_kernel(const bf16_t *__restrict__ A, const bf16_t *__restrict__ W
   int frag_off[KS];
 #pragma unroll
   for (int kk = 0; kk < KS; ++kk) frag_off[kk] = fr * kRowBytes + (((kk * 2 + fh) ^ swz) << 4);
-  const int a_base = wm * (BM / 2) * kRowBytes;              // byte offset of the wave's rows in the A tile
-  const int w_base = kATile + wn * (BN / 2) * kRowBytes;
+  const int a_base = wm * (BM / WM) * kRowBytes;             // byte offset of the wave's rows in the A tile
+  const int w_base = kATile + wn * (BN / WN) * kRowBytes;
 
   floatx16 acc[NT][MT];                                      // [n sub-tile][m sub-tile]
 #pragma unroll
@@ -143,7 +147,10 @@ gemm_bf16_mfma_kernel(const bf16_t *__restrict__ A, const bf16_t *__restrict__ W
   const int nk = K / BK;
 #pragma unroll
   for (int s = 0; s < kStages - 1; ++s)
-    if (s < nk) issue_loads(s);
+    if (s < nk) {
+#pragma unroll
+      for (int i = 0; i < kLoadsPerStage; ++i) issue_one(s, i);
+    }
 
   // Waits until at most n whole stages of this wave's direct loads are still in flight.
   auto wait_stages = [&](int n) {
@@ -151,57 +158,60 @@ gemm_bf16_mfma_kernel(const bf16_t *__restrict__ A, const bf16_t *__restrict__ W
     else if (kStages >= 3 && n >= 1) wait_vmcnt<kLoadsPerStage>();
     else wait_vmcnt<0>();
   };
-  auto read_frags = [&](const unsigned char *stage, int kk, bf16x8 (&af)[MT], bf16x8 (&wf)[NT]) {
-#pragma unroll
-    for (int t = 0; t < MT; ++t)
-      af[t] = *reinterpret_cast<const bf16x8 *>(stage + a_base + t * 32 * kRowBytes + frag_off[kk]);
-#pragma unroll
-    for (int t = 0; t < NT; ++t)
-      wf[t] = *reinterpret_cast<const bf16x8 *>(stage + w_base + t * 32 * kRowBytes + frag_off[kk]);
+  // Fragment j of a k-step in the order the MFMAs below first need them: W 0, A 0..MT-1, W 1..
+  bf16x8 af[2][MT], wf[2][NT];
+  auto read_one = [&](const unsigned char *stage, int kk, int buf, int j) {
+    if (j == 0) wf[buf][0] = *reinterpret_cast<const bf16x8 *>(stage + w_base + frag_off[kk]);
+    else if (j <= MT) af[buf][j - 1] = *reinterpret_cast<const bf16x8 *>(stage + a_base + (j - 1) * 32 * kRowBytes + frag_off[kk]);
+    else wf[buf][j - MT] = *reinterpret_cast<const bf16x8 *>(stage + w_base + (j - MT) * 32 * kRowBytes + frag_off[kk]);
   };
 
-  // Software pipeline over k-steps (16 k each).  Invariant at the top of a stage: its first
-  // fragments are already in registers.
-  //  * fragments of k-step kk+1 are read while the MFMAs of k-step kk run; in the LAST k-step of
-  //    stage kt the wave first waits for its own direct loads of stage kt+1, passes the block's
-  //    one barrier per stage, and reads the first fragments of stage kt+1 -- so neither the
-  //    barrier nor the LDS latency after it leaves the MFMA pipe empty;
-  //  * that barrier also frees ring slot kt % kStages; the direct loads that refill it (stage
-  //    kt + kStages) are issued during the first KS-1 k-steps of stage kt+1, a few per group of
-  //    MT MFMAs rather than in one burst: a wave issues in order, and sixteen back-to-back
-  //    vector-memory instructions from each of four waves stall the MFMAs queued behind them.
-  constexpr int kGroups = (KS - 1) * NT;
-  constexpr int kPerGroup = (kLoadsPerStage + kGroups - 1) / kGroups;
-  bf16x8 af[2][MT], wf[2][NT];
+  // Software pipeline over k-steps (16 k each), written out in issue order and pinned with
+  // sched_barrier after every MFMA: a wave issues in order, so whatever stands between two
+  // MFMAs must fit into the 32 cycles the first one keeps the matrix pipe busy.  After MFMA i
+  // of a k-step come at most one LDS read (fragment i of the NEXT k-step, double-buffered in
+  // registers) and the direct loads that fall to it (the refill of the ring slot freed by the
+  // last barrier, spread over the first KS-1 k-steps instead of one burst).  In the LAST k-step
+  // of stage kt the wave first waits for its own direct loads of stage kt+1 and passes the
+  // block's one barrier per stage; the fragments it then reads are the first ones of stage kt+1.
+  // A steady stage (one that still prefetches) has compile-time wait counts and no branches.
+  constexpr int kMfmaPerStep = MT * NT, kDsPerStep = MT + NT;
+  constexpr int kVmPerStep = (kLoadsPerStage + KS - 2) / (KS - 1);
+  static_assert(kDsPerStep <= kMfmaPerStep, "one LDS read per MFMA");
   wait_stages(min(kStages - 2, nk - 1));
   __builtin_amdgcn_s_barrier();
-  read_frags(lds, 0, af[0], wf[0]);
-  auto run_stage = [&](int kt, auto with_loads) {
+#pragma unroll
+  for (int j = 0; j < kDsPerStep; ++j) read_one(lds, 0, 0, j);
+  auto run_stage = [&](int kt, auto steady) {
+    constexpr bool kSteady = decltype(steady)::value;
     const unsigned char *stage = lds + (kt % kStages) * kStage;
+    const unsigned char *next = lds + ((kt + 1) % kStages) * kStage;
 #pragma unroll
     for (int kk = 0; kk < KS; ++kk) {
       const int cur = kk & 1, nxt = cur ^ 1;
-      if (kk + 1 < KS) {
-        read_frags(stage, kk + 1, af[nxt], wf[nxt]);
-      } else if (kt + 1 < nk) {
-        wait_stages(min(kStages - 2, nk - 2 - kt));          // stage kt+1 has landed (my part of it)
+      const bool last = kk + 1 == KS;
+      const bool more = !last || kSteady || kt + 1 < nk;     // is there a next k-step to read for
+      if (last && more) {
+        if (kSteady) wait_vmcnt<(kStages - 2) * kLoadsPerStage>();   // stage kt+1 has landed (my part of it)
+        else wait_stages(min(kStages - 2, nk - 2 - kt));
         __builtin_amdgcn_s_waitcnt(0xc07f);                  // lgkmcnt(0): my reads of stage kt are done
         // Raw barrier (no fence): every wave has waited for its own direct loads and LDS reads.
         __builtin_amdgcn_s_barrier();
-        read_frags(lds + ((kt + 1) % kStages) * kStage, 0, af[nxt], wf[nxt]);
       }
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int nt = 0; nt < NT; ++nt) {
-        if (decltype(with_loads)::value && kk + 1 < KS) {
+      for (int i = 0; i < kMfmaPerStep; ++i) {
+        const int nt = i / MT, mt = i % MT;
+        acc[nt][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[cur][nt], af[cur][mt], acc[nt][mt], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        if (more && i < kDsPerStep) read_one(last ? next : stage, last ? 0 : kk + 1, nxt, i);
+        if (kSteady && !last) {
 #pragma unroll
-          for (int q = 0; q < kPerGroup; ++q) {
-            const int i = (kk * NT + nt) * kPerGroup + q;
-            if (i < kLoadsPerStage) issue_one(kt + kStages - 1, i);
-          }
+          for (int q = 0; q < kVmPerStep; ++q)
+            if ((q * kMfmaPerStep) / kVmPerStep == i && kk * kVmPerStep + q < kLoadsPerStage)
+              issue_one(kt + kStages - 1, kk * kVmPerStep + q);
         }
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
-          acc[nt][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[cur][nt], af[cur][mt], acc[nt][mt], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
       }
     }
   };
@@ -210,14 +220,28 @@ gemm_bf16_mfma_kernel(const bf16_t *__restrict__ A, const bf16_t *__restrict__ W
   for (; kt < n_loading; ++kt) run_stage(kt, std::true_type{});
   for (; kt < nk; ++kt) run_stage(kt, std::false_type{});
 
-  // ---- epilogue: lane holds, for sub-tile (nt, mt) and group i, the 4 consecutive columns
-  //      nt*32 + 8*i + 4*(lane/32) + {0..3} of row mt*32 + lane%32 ----
+  // ---- epilogue ----
+  // A lane holds, for sub-tile (nt, mt) and group i, the 4 consecutive columns
+  // nt*32 + 8*i + 4*(lane/32) + {0..3} of row mt*32 + lane%32: one row per lane, so a direct
+  // store would touch 32 rows with 8 bytes each.  Instead each wave turns 32 rows at a time
+  // around through its own piece of the (now free) LDS ring and stores 16 bytes per lane with
+  // consecutive lanes along a row (whole 128-byte lines).  Staging is bf16 except for the
+  // residual epilogue, which stages float32 so that acc + residual is rounded once.
+  constexpr int WTM = BM / WM, WTN = BN / WN;
+  constexpr int OC = (EPI == kEpiSwiglu) ? WTN / 2 : WTN;            // output columns of this wave
+  constexpr int kElem = (EPI == kEpiResidual) ? 4 : 2;
+  constexpr int kStride = OC * kElem + 16;                           // padded row of the staging area
+  constexpr int LPR = OC / 8;                                        // lanes per output row (8 columns each)
+  constexpr int kRowsPerInstr = 64 / LPR;
+  static_assert(WM * WN * 32 * kStride <= kStages * kStage, "staging area exceeds the LDS ring");
+  __syncthreads();                                                   // every wave is done with the ring
+  unsigned char *my = lds + wave * (32 * kStride);
+  const int out_col0 = (EPI == kEpiSwiglu ? tile_n * (BN / 2) : tile_n * BN) + wn * OC;
+  const int rd_row = lane / LPR, rd_col = (lane % LPR) * 8;
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt) {
-    const int m = m0 + wm * (BM / 2) + mt * 32 + fr;
-    if (m >= M) continue;
+    unsigned char *wrow = my + fr * kStride;
     if (EPI == kEpiSwiglu) {
-      bf16_t *crow = C + (int64_t)m * N_out + tile_n * (BN / 2) + wn * (BN / 4);
 #pragma unroll
       for (int p = 0; p < NT / 2; ++p)
 #pragma unroll
@@ -225,38 +249,54 @@ gemm_bf16_mfma_kernel(const bf16_t *__restrict__ A, const bf16_t *__restrict__ W
           float v[4];
 #pragma unroll
           for (int j = 0; j < 4; ++j) v[j] = silu_f(acc[2 * p][mt][4 * i + j]) * acc[2 * p + 1][mt][4 * i + j];
-          uint2 o = make_uint2(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]));
-          *reinterpret_cast<uint2 *>(crow + p * 32 + 8 * i + 4 * fh) = o;
+          *reinterpret_cast<uint2 *>(wrow + (p * 32 + 8 * i + 4 * fh) * 2) =
+              make_uint2(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]));
         }
     } else {
-      const int64_t off = (int64_t)m * N_out + tile_n * BN + wn * (BN / 2);
 #pragma unroll
       for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-          const int64_t o = off + nt * 32 + 8 * i + 4 * fh;
-          float v[4];
-#pragma unroll
-          for (int j = 0; j < 4; ++j) v[j] = acc[nt][mt][4 * i + j];
-          if (EPI == kEpiResidual) {
-            const uint2 r = *reinterpret_cast<const uint2 *>(Res + o);
-            v[0] += __uint_as_float(r.x << 16); v[1] += __uint_as_float(r.x & 0xffff0000u);
-            v[2] += __uint_as_float(r.y << 16); v[3] += __uint_as_float(r.y & 0xffff0000u);
-          }
-          *reinterpret_cast<uint2 *>(C + o) = make_uint2(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]));
+          const int col = nt * 32 + 8 * i + 4 * fh;
+          if (EPI == kEpiResidual)
+            *reinterpret_cast<float4 *>(wrow + col * 4) = make_float4(acc[nt][mt][4 * i], acc[nt][mt][4 * i + 1],
+                                                                     acc[nt][mt][4 * i + 2], acc[nt][mt][4 * i + 3]);
+          else
+            *reinterpret_cast<uint2 *>(wrow + col * 2) = make_uint2(pack_bf16x2(acc[nt][mt][4 * i], acc[nt][mt][4 * i + 1]),
+                                                                   pack_bf16x2(acc[nt][mt][4 * i + 2], acc[nt][mt][4 * i + 3]));
         }
+    }
+#pragma unroll
+    for (int j = 0; j < 32 / kRowsPerInstr; ++j) {
+      const int r = j * kRowsPerInstr + rd_row;
+      const int m = m0 + wm * WTM + mt * 32 + r;
+      const int64_t o = (int64_t)m * N_out + out_col0 + rd_col;
+      uint4 out;
+      if (EPI == kEpiResidual) {
+        const float4 x0 = *reinterpret_cast<const float4 *>(my + r * kStride + rd_col * 4);
+        const float4 x1 = *reinterpret_cast<const float4 *>(my + r * kStride + rd_col * 4 + 16);
+        uint4 rs = make_uint4(0, 0, 0, 0);
+        if (m < M) rs = *reinterpret_cast<const uint4 *>(Res + o);
+        out.x = pack_bf16x2(x0.x + __uint_as_float(rs.x << 16), x0.y + __uint_as_float(rs.x & 0xffff0000u));
+        out.y = pack_bf16x2(x0.z + __uint_as_float(rs.y << 16), x0.w + __uint_as_float(rs.y & 0xffff0000u));
+        out.z = pack_bf16x2(x1.x + __uint_as_float(rs.z << 16), x1.y + __uint_as_float(rs.z & 0xffff0000u));
+        out.w = pack_bf16x2(x1.z + __uint_as_float(rs.w << 16), x1.w + __uint_as_float(rs.w & 0xffff0000u));
+      } else {
+        out = *reinterpret_cast<const uint4 *>(my + r * kStride + rd_col * 2);
+      }
+      if (m < M) *reinterpret_cast<uint4 *>(C + o) = out;
     }
   }
 }
 
-template <int EPI, int BM, int BN, int BK, int ST>
+template <int EPI, int BM, int BN, int BK, int ST, int WM, int WN>
 pvf_status run(pvf_ctx *ctx, hipStream_t s, const void *A, const void *W, void *C, const void *Res,
                int M, int N_out, int K) {
   constexpr int kLdsBytes = ST * (BM + BN) * BK * 2;
   static_assert(kLdsBytes <= 160 * 1024, "LDS ring exceeds the 160 KB of a CU");
   static bool configured = false;
   if (!configured) {
-    PVF_HIP_CHECK(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(gemm_bf16_mfma_kernel<EPI, BM, BN, BK, ST>),
+    PVF_HIP_CHECK(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(gemm_bf16_mfma_kernel<EPI, BM, BN, BK, ST, WM, WN>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes));
     configured = true;
   }
@@ -264,25 +304,30 @@ pvf_status run(pvf_ctx *ctx, hipStream_t s, const void *A, const void *W, void *
   const int tiles_n = (EPI == kEpiSwiglu) ? N_out / (BN / 2) : N_out / BN;
   const int total = tiles_m * tiles_n;
   const int grid = 8 * ((total + 7) / 8);
-  gemm_bf16_mfma_kernel<EPI, BM, BN, BK, ST><<<grid, kThreads, kLdsBytes, s>>>(
+  gemm_bf16_mfma_kernel<EPI, BM, BN, BK, ST, WM, WN><<<grid, 64 * WM * WN, kLdsBytes, s>>>(
       (const bf16_t *)A, (const bf16_t *)W, (bf16_t *)C, (const bf16_t *)Res, M, N_out, K, tiles_m, tiles_n);
   PVF_LAUNCH_CHECK(ctx, "gemm_mfma");
   return PVF_OK;
 }
 
 struct TileCfg { int bm, bn, bk, stages; double eff; };
-constexpr int kNumCfg = 4;
+constexpr int kNumCfg = 6;
 constexpr TileCfg kCfg[kNumCfg] = {
-    {256, 256, 32, 4, 1.00}, {128, 256, 64, 3, 0.85}, {256, 128, 64, 3, 0.85}, {128, 128, 64, 4, 0.80}};
+    {256, 256, 32, 4, 1.00},   // 8 waves
+    {128, 256, 64, 3, 0.85}, {256, 128, 64, 3, 0.85}, {128, 128, 64, 4, 0.80},
+    {256, 256, 32, 4, 0.0},    // shape 0 with 4 waves (only when forced)
+    {192, 256, 32, 4, 0.97}};  // fills the chip when M / 256 leaves many CUs idle
 
 template <int EPI>
 pvf_status run_cfg(pvf_ctx *ctx, hipStream_t s, int cfg, const void *A, const void *W, void *C,
                    const void *Res, int M, int N, int K) {
   switch (cfg) {
-    case 0: return run<EPI, 256, 256, 32, 4>(ctx, s, A, W, C, Res, M, N, K);
-    case 1: return run<EPI, 128, 256, 64, 3>(ctx, s, A, W, C, Res, M, N, K);
-    case 2: return run<EPI, 256, 128, 64, 3>(ctx, s, A, W, C, Res, M, N, K);
-    default: return run<EPI, 128, 128, 64, 4>(ctx, s, A, W, C, Res, M, N, K);
+    case 0: return run<EPI, 256, 256, 32, 4, 2, 4>(ctx, s, A, W, C, Res, M, N, K);
+    case 1: return run<EPI, 128, 256, 64, 3, 2, 2>(ctx, s, A, W, C, Res, M, N, K);
+    case 2: return run<EPI, 256, 128, 64, 3, 2, 2>(ctx, s, A, W, C, Res, M, N, K);
+    case 3: return run<EPI, 128, 128, 64, 4, 2, 2>(ctx, s, A, W, C, Res, M, N, K);
+    case 4: return run<EPI, 256, 256, 32, 4, 2, 2>(ctx, s, A, W, C, Res, M, N, K);
+    default: return run<EPI, 192, 256, 32, 4, 2, 2>(ctx, s, A, W, C, Res, M, N, K);
   }
 }
 
@@ -298,6 +343,7 @@ int pick_config(GemmEpilogue epi, int M, int N, int K) {
     const int ncols = (epi == kEpiSwiglu) ? kCfg[c].bn / 2 : kCfg[c].bn;
     if (N % ncols != 0 || K % kCfg[c].bk != 0) continue;
     if (forced == c) return c;
+    if (kCfg[c].eff <= 0.0) continue;
     const int64_t tiles = (int64_t)((M + kCfg[c].bm - 1) / kCfg[c].bm) * (N / ncols);
     const double t = (double)((tiles + 255) / 256) * kCfg[c].bm * kCfg[c].bn / kCfg[c].eff;
     if (best < 0 || t < best_t) { best = c; best_t = t; }
@@ -309,6 +355,8 @@ int pick_config(GemmEpilogue epi, int M, int N, int K) {
 
 bool gemm_mfma_supported(int dtype, GemmEpilogue epi, int M, int N, int K) {
   if (dtype != PVF_BF16 || M < 1 || K < 64 || K % 64 != 0) return false;
+  const int64_t w_rows = (epi == kEpiSwiglu) ? 2 * (int64_t)N : N;
+  if ((int64_t)M * K * 2 >= (1ll << 32) || w_rows * K * 2 >= (1ll << 32)) return false;   // 32-bit lane offsets
   return N % (epi == kEpiSwiglu ? 64 : 128) == 0;
 }
 
