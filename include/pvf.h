@@ -53,8 +53,8 @@ typedef enum {
 } pvf_status;
 
 enum { PVF_F32 = 0, PVF_BF16 = 1 };
-enum { PVF_ROUTE_NONE = 0, PVF_ROUTE_PLAN = 1, PVF_ROUTE_AR = 2 };
-enum { PVF_ROUTES_PLAN = 1, PVF_ROUTES_AR = 2 };
+enum { PVF_ROUTE_NONE = 0, PVF_ROUTE_PLAN = 1, PVF_ROUTE_AR = 2, PVF_ROUTE_CAL = 3 };
+enum { PVF_ROUTES_PLAN = 1, PVF_ROUTES_AR = 2, PVF_ROUTES_CAL = 4 };
 
 typedef struct pvf_ctx pvf_ctx;
 
@@ -80,12 +80,17 @@ typedef struct {
   int32_t block_len;    /* tokens per block; gen_len % block_len == 0                  */
   int32_t prompt_len;
   int32_t gen_len;
-  int32_t routes;       /* bit 0 planning route, bit 1 AR route; 0 = threshold decoding */
+  int32_t routes;       /* bit 0 planning route, bit 1 AR route; 0 = threshold decoding; */
+                        /* PVF_ROUTES_CAL alone = calibration trajectory (App. A.2):    */
+                        /* threshold decoding whose drafts are the non-base masks with  */
+                        /* confidence in [tau_plan_lo, tau_plan_hi) (the calibration    */
+                        /* band, any token, the K most confident); they are measured    */
+                        /* (A_j, Delta H_j) into the token statistics, never committed  */
   int32_t n_sparse;     /* early cross-block revelation threshold N_s (App. A.4.1);     */
                         /* 0 = off: the working set is always the active block alone   */
 } pvf_decode_cfg;
 
-#define PVF_MAX_K 16
+#define PVF_MAX_K 32
 #define PVF_MAX_SUMMARIES 8192   /* (1+K) * R must not exceed this */
 
 /* Weights, all dev, in cfg.dtype.  Per-layer entries are HOST arrays of n_layers dev pointers.
@@ -120,6 +125,15 @@ typedef struct {
                         /*              threshold / planning route / AR route             */
   int32_t *done;        /* [G]          in/out: 1 once the canvas holds no mask; a done    */
                         /*              group is skipped                                  */
+  /* Calibration only (routes == PVF_ROUTES_CAL); may be NULL otherwise.  Sec. 3 "Verified
+   * information gain", App. A.2 "Token-level aggregation". */
+  float   *ent;         /* [G, 1+K, R]  out: entropy H_i (nats) per window row             */
+  double  *dh;          /* [G, K]       out: Delta H_j of THIS batch's drafts              */
+  uint32_t *cal_n;      /* [vocab]      in/out accumulators over all measured events whose  */
+  uint32_t *cal_m;      /*              candidate token is v: n_v (events), m_v (events     */
+  uint32_t *cal_a;      /*              with a non-empty impact set), sum of A_j, and       */
+  double  *cal_vig;     /* [vocab]      sum of VIG_j = A_j * Delta H_j.  The caller zeroes  */
+                        /*              them before the first round.                        */
 } pvf_state;
 
 typedef struct {
@@ -202,6 +216,19 @@ pvf_status pvf_decode(pvf_ctx *ctx, void *stream, const int32_t *prompt, int32_t
 pvf_status pvf_stage1(void *stream, const void *logits, int32_t logits_dtype, int64_t n_rows,
                       int32_t vocab, int32_t mask_id, float logit_scale, float *conf,
                       int32_t *tok);
+
+/* Entropy of the token distribution per row (Sec. 3, H_i): ent[r] = -sum_w p_w ln p_w with
+ * p = softmax(logit_scale * logits[r]) over all ids except mask_id.  ent dev float32 [n_rows]. */
+pvf_status pvf_entropy(void *stream, const void *logits, int32_t logits_dtype, int64_t n_rows,
+                       int32_t vocab, int32_t mask_id, float logit_scale, float *ent);
+
+/* Filtering rule of App. A.2: bit v of plan_bitmap (ceil(vocab/32) dev words, overwritten) is set
+ * iff v != mask_id, n_v >= n_min, m_v >= m_min, a_v / m_v >= rho_ver and vig_v / n_v >= gamma_vig
+ * (ratios in float64; a ratio with a zero denominator counts as 0).  Inputs are the accumulators of pvf_state, all dev. */
+pvf_status pvf_plan_vocab_select(void *stream, const uint32_t *cal_n, const uint32_t *cal_m,
+                                 const uint32_t *cal_a, const double *cal_vig, int32_t vocab,
+                                 int32_t mask_id, uint32_t n_min, uint32_t m_min, float rho_ver,
+                                 float gamma_vig, uint32_t *plan_bitmap);
 
 /* C[M,N] = A[M,K] * W[N,K]^T (+ residual[M,N]); all dev, dtype PVF_F32 / PVF_BF16.
  * residual may be NULL and may alias C. */

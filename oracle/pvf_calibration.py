@@ -201,3 +201,91 @@ def select_margin(stats: TokenStats, rho_ver: float = 0.9, gamma_vig: float = 0.
         d2 = np.abs(stats.vig_hat - float(np.float32(gamma_vig))) / np.maximum(np.abs(stats.vig_hat), abs(float(gamma_vig)))
     d2 = np.where(np.isfinite(d2), d2, np.inf)
     return np.where(stats.n > 0, np.minimum(d1, d2), np.inf)
+
+
+# =============================================================================
+# the same trajectory with one batched forward per step (reading R2 of pvf_oracle.py)
+# =============================================================================
+ROUTE_CAL = 3
+
+
+def cal_summaries(state: O.State, forward_fn: O.ForwardFn, cfg: O.DecodeCfg, scale: float,
+                  mask_id: int) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
+    """(p, yhat, H) [1+K_t, R] of the backbone and of every measured branch on the window rows."""
+    wp = O.window_positions(cfg, state.k_active)
+    ok = wp < cfg.T
+    X = O.branch_canvases(state.y, O.Drafts(O.ROUTE_PLAN, state.drafts.fills) if state.drafts.n else O.Drafts())
+    conf = np.zeros((len(X), cfg.window_rows), np.float32)
+    tok = np.full((len(X), cfg.window_rows), -1, np.int32)
+    ent = np.zeros((len(X), cfg.window_rows), np.float32)
+    for j, x in enumerate(X):
+        lg = forward_fn(x)[wp[ok]]
+        conf[j, ok], tok[j, ok] = O.stage1(lg, scale, mask_id)
+        ent[j, ok] = entropy(lg, scale, mask_id)
+    return conf, tok, ent
+
+
+def cal_decide(state: O.State, conf: np.ndarray, tok: np.ndarray, ent: np.ndarray, cfg: O.DecodeCfg,
+               mask_id: int, band: Tuple[float, float], cap: Optional[int],
+               stats: Optional[TokenStats] = None) -> Tuple[O.State, List[Event]]:
+    """One step of the pipelined calibration trajectory: measure this batch's branches against
+    the backbone (= z_base of the step that proposed them), then do the next step's threshold
+    commit on the backbone's own predictions and pick its candidates.  state.drafts holds the
+    candidates as fills with route ROUTE_CAL; nothing but base tokens is ever committed."""
+    f32 = np.float32
+    bl = cfg.block_len
+    w0 = cfg.prompt_len + state.k_active * bl
+    events: List[Event] = []
+    if state.drafts.n:
+        B = list(range(w0, w0 + state.ws * bl))
+        n = len(B)
+        if stats is not None:
+            for q in range(n):
+                if state.y[B[q]] == mask_id:
+                    stats.cmp(conf[0][q], cfg.tau_high)
+        events = verify_events(state.y, B, conf[0][:n], tok[0][:n], ent[0][:n], state.drafts.fills,
+                               [tok[j][:n] for j in range(1, 1 + state.drafts.n)],
+                               [ent[j][:n] for j in range(1, 1 + state.drafts.n)], cfg.tau_high, mask_id)
+    # the threshold step of plain decoding (commit, block advance, working set) on the backbone row
+    plain = O.DecodeCfg(block_len=bl, prompt_len=cfg.prompt_len, gen_len=cfg.gen_len, tau_high=cfg.tau_high,
+                        tau_plan_lo=0.0, tau_plan_hi=0.0, tau_ar_lo=cfg.tau_ar_lo, K=0, routes=0, n_sparse=cfg.n_sparse)
+    before = state.y.copy()
+    new, info = O.decide(O.State(state.y.copy(), O.Drafts(), state.k_active, state.done, state.ws),
+                         conf[:1], tok[:1], plain, mask_id, [])
+    if stats is not None:
+        stats.margin = min(stats.margin, info.margin)
+    fills: List[Tuple[int, int]] = []
+    if not new.done:
+        lo = cfg.prompt_len + new.k_active * bl
+        cand = [i for i in range(lo, lo + new.ws * bl)
+                if new.y[i] == mask_id and f32(band[0]) <= conf[0][i - w0] < f32(band[1])]
+        if stats is not None:
+            for i in range(lo, lo + new.ws * bl):
+                if new.y[i] == mask_id:
+                    stats.cmp(conf[0][i - w0], band[0]); stats.cmp(conf[0][i - w0], band[1])
+        cand.sort(key=lambda i: (-float(conf[0][i - w0]), i))
+        if cap is not None:
+            if stats is not None and len(cand) > cap:
+                stats.cmp(conf[0][cand[cap - 1] - w0], conf[0][cand[cap] - w0])
+            cand = cand[:cap]
+        fills = [(i, int(tok[0][i - w0])) for i in cand]
+    assert np.all((before == new.y) | (before == mask_id))
+    return O.State(new.y, O.Drafts(ROUTE_CAL if fills else O.ROUTE_NONE, fills), new.k_active, new.done, new.ws), events
+
+
+def calibrate_pipelined(prompts: Sequence[Sequence[int]], forward_fn: O.ForwardFn, cfg: O.DecodeCfg,
+                        scale: float, mask_id: int, vocab: int, band: Tuple[float, float] = (0.15, 0.25),
+                        cap: Optional[int] = None) -> Tuple[TokenStats, List[np.ndarray], int]:
+    """`calibrate` with one batched forward per step.  Returns (stats, finals, rounds)."""
+    stats = TokenStats.zeros(vocab)
+    finals, rounds = [], 0
+    for prompt in prompts:
+        st = O.initial_state(prompt, cfg, mask_id)
+        while not st.done:
+            conf, tok, ent = cal_summaries(st, forward_fn, cfg, scale, mask_id)
+            st, events = cal_decide(st, conf, tok, ent, cfg, mask_id, band, cap, stats)
+            for ev in events:
+                stats.add(ev)
+            rounds += 1
+        finals.append(st.y)
+    return stats, finals, rounds

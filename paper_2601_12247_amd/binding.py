@@ -17,6 +17,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libpvf.so")
 
 PVF_F32, PVF_BF16 = 0, 1
+PVF_ROUTES_PLAN, PVF_ROUTES_AR, PVF_ROUTES_CAL = 1, 2, 4
+PVF_ROUTE_NONE, PVF_ROUTE_PLAN, PVF_ROUTE_AR, PVF_ROUTE_CAL = 0, 1, 2, 3
 ROUTE_NONE, ROUTE_PLAN, ROUTE_AR = 0, 1, 2
 MAX_K = 16
 STATUS = {0: "PVF_OK", -1: "PVF_EINVAL", -2: "PVF_ESHAPE", -3: "PVF_ENOMEM", -4: "PVF_EHIP",
@@ -26,7 +28,8 @@ STATUS = {0: "PVF_OK", -1: "PVF_EINVAL", -2: "PVF_ESHAPE", -3: "PVF_ENOMEM", -4:
 EXPORTS = ["pvf_create", "pvf_destroy", "pvf_last_error", "pvf_workspace_bytes", "pvf_profile_begin",
            "pvf_profile_end", "pvf_forward",
            "pvf_epilogue", "pvf_round", "pvf_state_init", "pvf_decode", "pvf_stage1", "pvf_gemm",
-           "pvf_gemm_swiglu", "pvf_rmsnorm", "pvf_rope_attention", "pvf_fill_normal"]
+           "pvf_gemm_swiglu", "pvf_rmsnorm", "pvf_rope_attention", "pvf_fill_normal", "pvf_entropy",
+           "pvf_plan_vocab_select"]
 
 
 class PvfError(RuntimeError):
@@ -59,7 +62,8 @@ class StateC(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in
                 ("canvas", "n_drafts", "draft_route", "fill_pos", "fill_tok", "k_active", "n_ws_blocks",
                  "conf",
-                 "tok", "accept", "winner", "n_commit", "done")]
+                 "tok", "accept", "winner", "n_commit", "done", "ent", "dh", "cal_n", "cal_m", "cal_a",
+                 "cal_vig")]
 
 
 class StatsC(C.Structure):
@@ -107,6 +111,11 @@ def lib() -> C.CDLL:
                                  C.POINTER(StatsC)]
         L.pvf_stage1.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int64, C.c_int32,
                                  C.c_int32, C.c_float, C.c_void_p, C.c_void_p]
+        L.pvf_entropy.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int64, C.c_int32,
+                                  C.c_int32, C.c_float, C.c_void_p]
+        L.pvf_plan_vocab_select.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                            C.c_int32, C.c_int32, C.c_uint32, C.c_uint32, C.c_float,
+                                            C.c_float, C.c_void_p]
         L.pvf_gemm.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
                                C.c_void_p, C.c_int32, C.c_int32, C.c_int32]
         L.pvf_gemm_swiglu.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
@@ -180,7 +189,7 @@ class DecodeCfg:
 class State:
     """Device buffers of pvf_state for G groups (allocated with torch)."""
 
-    def __init__(self, G: int, cfg: DecodeCfg, device="cuda"):
+    def __init__(self, G: int, cfg: DecodeCfg, device="cuda", vocab: Optional[int] = None):
         K, T, R = cfg.K, cfg.T, cfg.R
         i32 = dict(dtype=torch.int32, device=device)
         self.G, self.cfg = G, cfg
@@ -197,6 +206,16 @@ class State:
         self.winner = torch.zeros(G, **i32)
         self.n_commit = torch.zeros(G, 3, **i32)
         self.done = torch.zeros(G, **i32)
+        # calibration members (App. A.2): allocated only for the calibration trajectory
+        self.ent = self.dh = self.cal_n = self.cal_m = self.cal_a = self.cal_vig = None
+        if cfg.routes & PVF_ROUTES_CAL:
+            assert vocab is not None, "the calibration trajectory needs vocab for the token statistics"
+            self.ent = torch.zeros(G, 1 + K, R, dtype=torch.float32, device=device)
+            self.dh = torch.zeros(G, max(K, 1), dtype=torch.float64, device=device)
+            self.cal_n = torch.zeros(vocab, **i32)
+            self.cal_m = torch.zeros(vocab, **i32)
+            self.cal_a = torch.zeros(vocab, **i32)
+            self.cal_vig = torch.zeros(vocab, dtype=torch.float64, device=device)
 
     def c(self) -> StateC:
         return StateC(*[_ptr(getattr(self, n)) for n, _ in StateC._fields_])
@@ -305,6 +324,26 @@ def stage1(logits: torch.Tensor, mask_id: int, logit_scale: float, conf: Optiona
     _check(lib().pvf_stage1(_stream(), _ptr(logits), _dtype_code(logits.dtype), n, V, mask_id,
                             logit_scale, _ptr(conf), _ptr(tok)))
     return conf, tok
+
+
+def entropy(logits: torch.Tensor, mask_id: int, logit_scale: float = 1.0) -> torch.Tensor:
+    """H_i (nats) of softmax(logit_scale * logits[i]) over all ids but mask_id; logits [n, V]."""
+    n, V = logits.shape
+    ent = torch.empty(n, dtype=torch.float32, device=logits.device)
+    _check(lib().pvf_entropy(_stream(), _ptr(logits), _dtype_code(logits.dtype), n, V, mask_id,
+                             logit_scale, _ptr(ent)))
+    return ent
+
+
+def plan_vocab_select(cal_n: torch.Tensor, cal_m: torch.Tensor, cal_a: torch.Tensor, cal_vig: torch.Tensor,
+                      mask_id: int, n_min: int = 50, m_min: int = 20, rho_ver: float = 0.9,
+                      gamma_vig: float = 0.03) -> torch.Tensor:
+    """Filtering rule of App. A.2 on the accumulated token statistics -> planning bitmap."""
+    V = cal_n.numel()
+    bitmap = torch.empty((V + 31) // 32, dtype=torch.int32, device=cal_n.device)
+    _check(lib().pvf_plan_vocab_select(_stream(), _ptr(cal_n), _ptr(cal_m), _ptr(cal_a), _ptr(cal_vig), V,
+                                       mask_id, n_min, m_min, rho_ver, gamma_vig, _ptr(bitmap)))
+    return bitmap
 
 
 def gemm(A: torch.Tensor, W: torch.Tensor, residual: Optional[torch.Tensor] = None,

@@ -16,6 +16,7 @@ SOURCES = [
     "pvf_api.hip",
     "epilogue.hip",
     "decision.hip",
+    "calibration.hip",
     "elementwise.hip",
     "gemm_simple.hip",
     "gemm_mfma.hip",

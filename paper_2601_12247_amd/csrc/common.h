@@ -68,12 +68,35 @@ struct RowFilter {
   int32_t R, prompt_len, block_len, T;
 };
 
+// Where a logits row's summary goes and whether the row exists at all.
+__device__ __forceinline__ bool row_target(const RowFilter &rf, int64_t row, int64_t *out_row) {
+  *out_row = row;
+  if (rf.n_drafts == nullptr) return true;
+  const int s = (int)(row / rf.R), r = (int)(row % rf.R);
+  const int slot = rf.seq_slot ? rf.seq_slot[s] : s;
+  const int g = slot / rf.slots_per_group, j = slot % rf.slots_per_group;
+  *out_row = (int64_t)slot * rf.R + r;
+  if (rf.done[g] || j > rf.n_drafts[g]) return false;
+  return rf.prompt_len + rf.k_active[g] * rf.block_len + r < rf.T;
+}
+
 pvf_status launch_stage1(pvf_ctx *ctx, hipStream_t s, const void *logits, int dtype,
                          int64_t n_rows, int vocab, int mask_id, float scale,
                          const RowFilter &rf, float *conf, int32_t *tok);
 
 // rows of the decision window: min(c * block_len, gen_len), c = 2, or 4 with n_sparse > 0
 int window_rows(const pvf_decode_cfg &c);
+
+// entropy per logits row (calibration only); rows are filtered like stage 1
+pvf_status launch_entropy(pvf_ctx *ctx, hipStream_t s, const void *logits, int dtype,
+                          int64_t n_rows, int vocab, int mask_id, float scale,
+                          const RowFilter &rf, float *ent);
+
+pvf_status launch_plan_vocab_select(pvf_ctx *ctx, hipStream_t s, const uint32_t *cal_n,
+                                    const uint32_t *cal_m, const uint32_t *cal_a,
+                                    const double *cal_vig, int vocab, int mask_id, uint32_t n_min,
+                                    uint32_t m_min, float rho_ver, float gamma_vig,
+                                    uint32_t *plan_bitmap);
 
 pvf_status launch_stage2(pvf_ctx *ctx, hipStream_t s, int G, int vocab, int mask_id,
                          const uint32_t *plan_bitmap, const pvf_decode_cfg &cfg,

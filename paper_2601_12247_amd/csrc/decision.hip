@@ -12,6 +12,13 @@
 //            (Sec. 4.3), and the next batch of canvases (Eq. plan_branch / AR branches).
 // Everything is integer / compare work on at most (1+K) * R summaries; C_total is summed in
 // float64, which is exact for these inputs and therefore independent of the order.
+//
+// Calibration trajectory (App. A.2; routes == PVF_ROUTES_CAL): the same machinery with two
+// changes.  propose: the drafts are the non-base masks whose confidence lies in the calibration
+// band, whatever their token, the K most confident first.  verify: each draft is only measured
+// -- A_j as above and Delta H_j, the mean entropy drop over the masked positions of the working
+// set other than the draft's own (Sec. 3) -- and added to the token statistics n_v, m_v, sum A,
+// sum A * Delta H of its token v; nothing but the base branch is ever committed.
 #include "common.h"
 
 namespace pvf {
@@ -103,6 +110,32 @@ __global__ void __launch_bounds__(kStage2Threads) stage2_kernel(Stage2Args a) {
       }
       s_ok[j - 1] = ok;
       s_C[j - 1] = C;
+    }
+  } else if (route == PVF_ROUTE_CAL) {
+    for (int i = tid; i < wlen; i += nth) {
+      const int imp = (s_x[i] == MASK) && (s_conf[i] >= a.cfg.tau_high);
+      s_flag[i] = imp;
+      if (imp) atomicAdd(&s_cnt[0], 1);
+    }
+    __syncthreads();
+    if (tid >= 1 && tid <= Kt) {          // one thread per measured draft
+      const int j = tid, fp = s_fpos[j - 1], v = s_ftok[j - 1];
+      bool ok = (s_cnt[0] > 0) && (fp >= 0);
+      const float *ent0 = a.st.ent + (int64_t)g * slots * R, *entj = ent0 + (int64_t)j * R;
+      double sum = 0.0;
+      int cnt = 0;
+      for (int i = 0; i < wlen; ++i) {
+        if (s_flag[i] && s_tok[j * R + i] != s_tok[i]) ok = false;
+        if (s_x[i] == MASK && i != fp) { sum += (double)ent0[i] - (double)entj[i]; ++cnt; }
+      }
+      const double dH = cnt ? sum / cnt : 0.0;
+      s_ok[j - 1] = ok;
+      a.st.dh[(int64_t)g * K + j - 1] = dH;
+      if (fp >= 0 && v >= 0 && v < a.vocab) {
+        atomicAdd(&a.st.cal_n[v], 1u);
+        if (s_cnt[0] > 0) atomicAdd(&a.st.cal_m[v], 1u);
+        if (ok) { atomicAdd(&a.st.cal_a[v], 1u); atomicAdd(&a.st.cal_vig[v], dH); }
+      }
     }
   } else if (route == PVF_ROUTE_AR) {
     if (tid >= 1 && tid <= Kt) {
@@ -217,6 +250,24 @@ __global__ void __launch_bounds__(kStage2Threads) stage2_kernel(Stage2Args a) {
           }
         }
       }
+      if (a.cfg.routes & PVF_ROUTES_CAL) {
+        for (int i = tid; i < plen; i += nth)
+          if (s_flag[i] == 1 && cw[i] >= a.cfg.tau_plan_lo && cw[i] < a.cfg.tau_plan_hi) {
+            s_cand[i] = 3; atomicAdd(&s_cnt[2], 1);
+          }
+        __syncthreads();
+        if (s_cnt[2] > 0) {
+          route_next = PVF_ROUTE_CAL;
+          K_next = min(K, s_cnt[2]);
+          for (int i = tid; i < plen; i += nth) {  // rank by (-confidence, position)
+            if (s_cand[i] != 3) continue;
+            int rank = 0;
+            for (int i2 = 0; i2 < plen; ++i2)
+              if (s_cand[i2] == 3 && (cw[i2] > cw[i] || (cw[i2] == cw[i] && i2 < i))) ++rank;
+            if (rank < K) { s_npos[rank] = w0 + off + i; s_ntok[rank] = tw[i]; }
+          }
+        }
+      }
       if (route_next == PVF_ROUTE_NONE && (a.cfg.routes & PVF_ROUTES_AR)) {
         for (int i = tid; i < plen; i += nth)
           if (s_flag[i] == 1 && cw[i] >= a.cfg.tau_ar_lo) { s_cand[i] = 4; atomicAdd(&s_cnt[2], 1); }
@@ -244,7 +295,7 @@ __global__ void __launch_bounds__(kStage2Threads) stage2_kernel(Stage2Args a) {
     if (pos >= T) continue;
     int v = s_x[r];
     if (j >= 1 && j <= K_next) {
-      if (route_next == PVF_ROUTE_PLAN) { if (s_npos[j - 1] == pos) v = s_ntok[j - 1]; }
+      if (route_next != PVF_ROUTE_AR) { if (s_npos[j - 1] == pos) v = s_ntok[j - 1]; }
       else { for (int q = 0; q < j; ++q) if (s_npos[q] == pos) v = s_ntok[q]; }
     }
     canvas0[(int64_t)j * T + pos] = v;

@@ -52,18 +52,6 @@ __device__ __forceinline__ uint4 load_stream(const uint4 *p) {
   return make_uint4(t.x, t.y, t.z, t.w);
 }
 
-// Where a logits row's summary goes and whether the row exists at all.
-__device__ __forceinline__ bool row_target(const RowFilter &rf, int64_t row, int64_t *out_row) {
-  *out_row = row;
-  if (rf.n_drafts == nullptr) return true;
-  const int s = (int)(row / rf.R), r = (int)(row % rf.R);
-  const int slot = rf.seq_slot ? rf.seq_slot[s] : s;
-  const int g = slot / rf.slots_per_group, j = slot % rf.slots_per_group;
-  *out_row = (int64_t)slot * rf.R + r;
-  if (rf.done[g] || j > rf.n_drafts[g]) return false;
-  return rf.prompt_len + rf.k_active[g] * rf.block_len + r < rf.T;
-}
-
 // Running (max, scaled sum) of one thread.  Values v live in the "compare domain": the raw
 // logit for bf16 rows (scaling by a positive factor keeps order and ties of bf16 values), or
 // logit_scale * logit for float rows.  Terms are 2^(v*c + nmc) with nmc = -fl(m*c); every

@@ -117,7 +117,9 @@ static pvf_status check_decode_cfg(pvf_ctx *ctx, const pvf_decode_cfg *c, int vo
   PVF_REQUIRE(ctx, c->tau_plan_lo <= c->tau_plan_hi && c->tau_plan_hi <= c->tau_high, PVF_EINVAL,
               "need tau_plan_lo <= tau_plan_hi <= tau_high (%g, %g, %g)", c->tau_plan_lo, c->tau_plan_hi, c->tau_high);
   PVF_REQUIRE(ctx, c->logit_scale > 0.f && std::isfinite(c->logit_scale), PVF_EINVAL, "logit_scale=%g must be positive", c->logit_scale);
-  PVF_REQUIRE(ctx, (c->routes & ~3) == 0, PVF_EINVAL, "routes=%d has unknown bits", c->routes);
+  PVF_REQUIRE(ctx, (c->routes & ~7) == 0, PVF_EINVAL, "routes=%d has unknown bits", c->routes);
+  PVF_REQUIRE(ctx, !(c->routes & PVF_ROUTES_CAL) || c->routes == PVF_ROUTES_CAL, PVF_EINVAL,
+              "routes=%d: the calibration trajectory excludes the planning and AR routes", c->routes);
   PVF_REQUIRE(ctx, c->n_sparse >= 0, PVF_EINVAL, "n_sparse=%d must be >= 0", c->n_sparse);
   PVF_REQUIRE(ctx, mask_id >= 0 && mask_id < vocab, PVF_EINVAL, "mask_id=%d outside [0,%d)", mask_id, vocab);
   PVF_REQUIRE(ctx, (int64_t)(1 + c->K) * window_rows(*c) <= PVF_MAX_SUMMARIES, PVF_ESHAPE,
@@ -125,8 +127,11 @@ static pvf_status check_decode_cfg(pvf_ctx *ctx, const pvf_decode_cfg *c, int vo
   return PVF_OK;
 }
 
-static pvf_status check_state(pvf_ctx *ctx, const pvf_state *st) {
+static pvf_status check_state(pvf_ctx *ctx, const pvf_state *st, const pvf_decode_cfg *cfg) {
   PVF_REQUIRE(ctx, st != nullptr, PVF_EINVAL, "state is NULL");
+  if (cfg->routes & PVF_ROUTES_CAL)
+    PVF_REQUIRE(ctx, st->ent && st->dh && st->cal_n && st->cal_m && st->cal_a && st->cal_vig, PVF_EINVAL,
+                "calibration needs the ent, dh and cal_* members of the state");
   PVF_REQUIRE(ctx, st->canvas && st->n_drafts && st->draft_route && st->fill_pos && st->fill_tok &&
                   st->k_active && st->n_ws_blocks && st->conf && st->tok && st->accept && st->winner && st->n_commit && st->done,
               PVF_EINVAL, "state has a NULL member");
@@ -301,6 +306,29 @@ extern "C" pvf_status pvf_stage1(void *stream, const void *logits, int32_t logit
   return launch_stage1(nullptr, (hipStream_t)stream, logits, logits_dtype, n_rows, vocab, mask_id, logit_scale, rf, conf, tok);
 }
 
+extern "C" pvf_status pvf_entropy(void *stream, const void *logits, int32_t logits_dtype,
+                                  int64_t n_rows, int32_t vocab, int32_t mask_id, float logit_scale,
+                                  float *ent) {
+  PVF_REQUIRE(nullptr, n_rows == 0 || (logits && ent), PVF_EINVAL, "pvf_entropy: NULL pointer");
+  PVF_REQUIRE(nullptr, logits_dtype == PVF_F32 || logits_dtype == PVF_BF16, PVF_EINVAL, "pvf_entropy: dtype=%d", logits_dtype);
+  PVF_REQUIRE(nullptr, n_rows >= 0 && vocab > 1, PVF_EINVAL, "pvf_entropy: n_rows=%lld vocab=%d", (long long)n_rows, vocab);
+  PVF_REQUIRE(nullptr, mask_id >= 0 && mask_id < vocab, PVF_EINVAL, "pvf_entropy: mask_id=%d outside [0,%d)", mask_id, vocab);
+  PVF_REQUIRE(nullptr, logit_scale > 0.f && std::isfinite(logit_scale), PVF_EINVAL, "pvf_entropy: logit_scale=%g", logit_scale);
+  RowFilter rf{};
+  return launch_entropy(nullptr, (hipStream_t)stream, logits, logits_dtype, n_rows, vocab, mask_id, logit_scale, rf, ent);
+}
+
+extern "C" pvf_status pvf_plan_vocab_select(void *stream, const uint32_t *cal_n, const uint32_t *cal_m,
+                                            const uint32_t *cal_a, const double *cal_vig, int32_t vocab,
+                                            int32_t mask_id, uint32_t n_min, uint32_t m_min, float rho_ver,
+                                            float gamma_vig, uint32_t *plan_bitmap) {
+  PVF_REQUIRE(nullptr, cal_n && cal_m && cal_a && cal_vig && plan_bitmap, PVF_EINVAL, "pvf_plan_vocab_select: NULL pointer");
+  PVF_REQUIRE(nullptr, vocab > 1 && mask_id >= 0 && mask_id < vocab, PVF_EINVAL, "pvf_plan_vocab_select: vocab=%d mask_id=%d", vocab, mask_id);
+  PVF_REQUIRE(nullptr, std::isfinite(rho_ver) && std::isfinite(gamma_vig), PVF_EINVAL, "pvf_plan_vocab_select: thresholds not finite");
+  return launch_plan_vocab_select(nullptr, (hipStream_t)stream, cal_n, cal_m, cal_a, cal_vig, vocab, mask_id,
+                                  n_min, m_min, rho_ver, gamma_vig, plan_bitmap);
+}
+
 static RowFilter make_filter(const pvf_decode_cfg &cfg, const pvf_state &st, const int32_t *seq_slot) {
   RowFilter rf;
   rf.n_drafts = st.n_drafts; rf.done = st.done; rf.k_active = st.k_active; rf.seq_slot = seq_slot;
@@ -314,7 +342,7 @@ extern "C" pvf_status pvf_epilogue(pvf_ctx *ctx, void *stream, const void *logit
                                    const pvf_decode_cfg *cfg, const pvf_state *state) {
   pvf_status st = check_decode_cfg(ctx, cfg, vocab, mask_id);
   if (st != PVF_OK) return st;
-  if ((st = check_state(ctx, state)) != PVF_OK) return st;
+  if ((st = check_state(ctx, state, cfg)) != PVF_OK) return st;
   PVF_REQUIRE(ctx, logits && plan_bitmap, PVF_EINVAL, "pvf_epilogue: NULL pointer");
   PVF_REQUIRE(ctx, logits_dtype == PVF_F32 || logits_dtype == PVF_BF16, PVF_EINVAL, "pvf_epilogue: dtype=%d", logits_dtype);
   PVF_REQUIRE(ctx, G >= 0, PVF_EINVAL, "pvf_epilogue: G=%d", G);
@@ -324,6 +352,10 @@ extern "C" pvf_status pvf_epilogue(pvf_ctx *ctx, void *stream, const void *logit
   const int64_t n_rows = (int64_t)G * (1 + cfg->K) * rf.R;
   st = launch_stage1(ctx, s, logits, logits_dtype, n_rows, vocab, mask_id, cfg->logit_scale, rf, state->conf, state->tok);
   if (st != PVF_OK) return st;
+  if (cfg->routes & PVF_ROUTES_CAL) {
+    st = launch_entropy(ctx, s, logits, logits_dtype, n_rows, vocab, mask_id, cfg->logit_scale, rf, state->ent);
+    if (st != PVF_OK) return st;
+  }
   return launch_stage2(ctx, s, G, vocab, mask_id, plan_bitmap, *cfg, *state);
 }
 
@@ -335,7 +367,7 @@ static pvf_status check_round(pvf_ctx *ctx, int G, const uint32_t *plan_bitmap, 
   PVF_REQUIRE(nullptr, ctx != nullptr, PVF_EINVAL, "ctx is NULL");
   pvf_status st = check_decode_cfg(ctx, cfg, ctx->model.vocab, ctx->model.mask_id);
   if (st != PVF_OK) return st;
-  if ((st = check_state(ctx, state)) != PVF_OK) return st;
+  if ((st = check_state(ctx, state, cfg)) != PVF_OK) return st;
   PVF_REQUIRE(ctx, plan_bitmap != nullptr, PVF_EINVAL, "plan_bitmap is NULL");
   PVF_REQUIRE(ctx, G > 0, PVF_EINVAL, "G=%d", G);
   const int T = cfg->prompt_len + cfg->gen_len;
@@ -361,6 +393,11 @@ static pvf_status round_impl(pvf_ctx *ctx, hipStream_t s, int G, const uint32_t 
                        ctx->model.mask_id, cfg.logit_scale, rf, state.conf, state.tok);
   }
   if (st != PVF_OK) return st;
+  if (cfg.routes & PVF_ROUTES_CAL) {
+    st = launch_entropy(ctx, s, ctx->logits, ctx->model.dtype, (int64_t)n_seq * R, ctx->model.vocab,
+                        ctx->model.mask_id, cfg.logit_scale, rf, state.ent);
+    if (st != PVF_OK) return st;
+  }
   return launch_stage2(ctx, s, G, ctx->model.vocab, ctx->model.mask_id, plan_bitmap, cfg, state);
 }
 
@@ -376,7 +413,7 @@ extern "C" pvf_status pvf_state_init(pvf_ctx *ctx, void *stream, const int32_t *
   PVF_REQUIRE(nullptr, ctx != nullptr, PVF_EINVAL, "ctx is NULL");
   pvf_status st = check_decode_cfg(ctx, cfg, ctx->model.vocab, ctx->model.mask_id);
   if (st != PVF_OK) return st;
-  if ((st = check_state(ctx, state)) != PVF_OK) return st;
+  if ((st = check_state(ctx, state, cfg)) != PVF_OK) return st;
   PVF_REQUIRE(ctx, G > 0 && (prompt || cfg->prompt_len == 0), PVF_EINVAL, "pvf_state_init: G=%d prompt=%p", G, (const void *)prompt);
   return launch_state_init(ctx, (hipStream_t)stream, prompt, G, ctx->model.mask_id, *cfg, *state);
 }

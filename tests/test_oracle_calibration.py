@@ -204,3 +204,25 @@ def test_filtering_rule_each_criterion():
     assert st.r_ver[6] == 0.0 and st.vig_hat[6] == 0.0
     mg = C.select_margin(st)
     assert mg[6] == np.inf and mg[0] < 1e-6 and mg[5] > 1e-2
+
+
+@pytest.mark.parametrize("seed,cap,ns", [(0, None, 0), (1, 3, 0), (2, 1, 0), (3, None, 2), (4, 2, 5)])
+def test_pipelined_schedule_gives_the_same_statistics(seed, cap, ns):
+    """One batched forward per step (backbone + measured branches) against the literal
+    two-forward procedure: same events, same statistics, same final canvases."""
+    V, mask_id = 14, 13
+    cfg = O.DecodeCfg(block_len=5, prompt_len=3, gen_len=15, tau_high=0.5, tau_plan_lo=0.0, tau_plan_hi=0.0,
+                      K=0, n_sparse=ns)
+    band = (0.12, 0.45)
+    fn = table_fn(V, seed, spread=2.0)
+    prompts = [[1, 2, 3], [4, 5, 6]]
+    a, fa, _ = C.calibrate(prompts, fn, cfg, 1.0, mask_id, V, band=band, cap=cap)
+    b, fb, rounds = C.calibrate_pipelined(prompts, fn, cfg, 1.0, mask_id, V, band=band, cap=cap)
+    assert a.n.sum() > 0
+    assert np.array_equal(a.n, b.n) and np.array_equal(a.m, b.m) and np.array_equal(a.a, b.a)
+    np.testing.assert_allclose(a.vig, b.vig, rtol=1e-12, atol=1e-15)
+    assert [(e.token, e.position, e.A) for e in a.events] == [(e.token, e.position, e.A) for e in b.events]
+    assert all(np.array_equal(x, y) for x, y in zip(fa, fb))
+    assert a.margin == pytest.approx(b.margin)
+    plain = [O.decode(p, fn, cfg, 1.0, mask_id, []).nfe for p in prompts]
+    assert rounds == sum(plain)                      # measuring never adds or removes a step
