@@ -88,6 +88,14 @@ typedef struct {
                         /* (A_j, Delta H_j) into the token statistics, never committed  */
   int32_t n_sparse;     /* early cross-block revelation threshold N_s (App. A.4.1);     */
                         /* 0 = off: the working set is always the active block alone   */
+  int32_t kv_cache;     /* 1 = block-level K/V cache (Sec. 5.1, "under KV cache"), used */
+                        /* by pvf_round / pvf_decode: a group gets the exact full       */
+                        /* forward in the first round and whenever its active block     */
+                        /* has changed, and that forward's per-layer rotated keys and   */
+                        /* values of the backbone canvas are kept; in all other rounds  */
+                        /* only the window rows of each canvas run through the layers   */
+                        /* and attend to the cached keys / values outside the window.   */
+                        /* 0 = every round is a full forward (exact)                    */
 } pvf_decode_cfg;
 
 #define PVF_MAX_K 32
@@ -188,7 +196,12 @@ pvf_status pvf_epilogue(pvf_ctx *ctx, void *stream, const void *logits, int32_t 
                         int32_t G, int32_t vocab, int32_t mask_id, const uint32_t *plan_bitmap,
                         const pvf_decode_cfg *cfg, const pvf_state *state);
 
-/* forward + epilogue on the same stream, no synchronisation in between.  n_seq_host: if
+/* With cfg->kv_cache = 1 the context keeps, per group, the cache and the block it was made for;
+ * pvf_state_init invalidates it.  Such a round first reads done / n_drafts / k_active back
+ * (one stream synchronisation) to split the groups into refreshing and cached ones; the
+ * cache memory (2 * n_layers * T * d_model elements per group) is allocated on first use.
+ *
+ * forward + epilogue on the same stream, no synchronisation in between.  n_seq_host: if
  * > 0, the caller's count of live canvases sum_g (done[g] ? 0 : 1 + n_drafts[g]) as read
  * from the state after the previous round; only those are forwarded.  If <= 0 all
  * G*(1+K) slots are forwarded (same results, more work). */

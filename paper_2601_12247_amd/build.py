@@ -17,6 +17,7 @@ SOURCES = [
     "epilogue.hip",
     "decision.hip",
     "calibration.hip",
+    "kvcache.hip",
     "elementwise.hip",
     "gemm_simple.hip",
     "gemm_mfma.hip",

@@ -110,6 +110,22 @@ pvf_status launch_build_batch(pvf_ctx *ctx, hipStream_t s, int G, int n_seq,
                               const pvf_decode_cfg &cfg, const pvf_state &st,
                               int32_t *seq_slot, int32_t *row_pos);
 
+// block-level K/V cache (kvcache.hip)
+pvf_status launch_fill_row_pos(pvf_ctx *ctx, hipStream_t s, const pvf_decode_cfg &cfg, const pvf_state &st,
+                               const int32_t *seq_slot, int n_seq, int32_t *row_pos);
+pvf_status launch_kv_store(pvf_ctx *ctx, hipStream_t s, int dtype, const void *qkv, const void *vt,
+                           const int32_t *seq_slot, int slots_per_group, int S, int T, int d,
+                           void *kc, void *vc, void *vtc, int64_t group_stride);
+pvf_status launch_embed_rows(pvf_ctx *ctx, hipStream_t s, int dtype, const void *embed, const int32_t *canvas,
+                             const int32_t *seq_slot, const int32_t *row_pos, int n_rows, int R, int T,
+                             int d, int vocab, void *out);
+pvf_status launch_rope_rows(pvf_ctx *ctx, hipStream_t s, int dtype, void *qkv, const int32_t *row_pos,
+                            int n_rows, int T, int n_heads, int d_head, const float2 *cos_sin);
+pvf_status launch_attention_window(pvf_ctx *ctx, hipStream_t s, int dtype, const void *qkv_w, const void *kc,
+                                   const void *vc, int64_t group_stride, const pvf_decode_cfg &cfg,
+                                   const pvf_state &st, const int32_t *seq_slot, int n_seq, int n_heads,
+                                   int d_head, void *out);
+
 pvf_status launch_copy_out(pvf_ctx *ctx, hipStream_t s, int G, int K, int T,
                            const int32_t *canvas, int32_t *out_tokens);
 

@@ -23,6 +23,13 @@ struct pvf_ctx {
   float2 *cos_sin = nullptr;           // [max_T, d_head/2]
   int32_t *status_host = nullptr;      // pinned, 2*G words per round
   int status_cap = 0;
+  // block-level K/V cache (decode_cfg.kv_cache): [G][n_layers][T][d] each, row-major like the
+  // k / v thirds of the qkv buffer; cache_block[g] = active block the cache of group g is for
+  void *kcache = nullptr, *vcache = nullptr;
+  int cache_G = 0, cache_T = 0;
+  std::vector<int> cache_block;
+  int32_t *seq_host = nullptr;         // pinned staging of the round's sequence list
+  int seq_host_cap = 0;
   int64_t ws_bytes = 0;
   char err[512] = {0};
   // optional per-kernel timing (pvf_profile_begin / pvf_profile_end)
@@ -121,6 +128,7 @@ static pvf_status check_decode_cfg(pvf_ctx *ctx, const pvf_decode_cfg *c, int vo
   PVF_REQUIRE(ctx, !(c->routes & PVF_ROUTES_CAL) || c->routes == PVF_ROUTES_CAL, PVF_EINVAL,
               "routes=%d: the calibration trajectory excludes the planning and AR routes", c->routes);
   PVF_REQUIRE(ctx, c->n_sparse >= 0, PVF_EINVAL, "n_sparse=%d must be >= 0", c->n_sparse);
+  PVF_REQUIRE(ctx, c->kv_cache == 0 || c->kv_cache == 1, PVF_EINVAL, "kv_cache=%d must be 0 or 1", c->kv_cache);
   PVF_REQUIRE(ctx, mask_id >= 0 && mask_id < vocab, PVF_EINVAL, "mask_id=%d outside [0,%d)", mask_id, vocab);
   PVF_REQUIRE(ctx, (int64_t)(1 + c->K) * window_rows(*c) <= PVF_MAX_SUMMARIES, PVF_ESHAPE,
               "(1+K)*R = %lld exceeds %d", (long long)(1 + c->K) * window_rows(*c), PVF_MAX_SUMMARIES);
@@ -148,9 +156,11 @@ using namespace pvf;
 static void free_ws(pvf_ctx *c) {
   for (hipEvent_t e : c->ev_pool) (void)hipEventDestroy(e);
   c->ev_pool.clear();
-  void *ptrs[] = {c->h, c->xn, c->qkv, c->att, c->act, c->vt, c->hrows, c->logits, c->seq_slot, c->row_pos, c->cos_sin};
+  void *ptrs[] = {c->h, c->xn, c->qkv, c->att, c->act, c->vt, c->hrows, c->logits, c->seq_slot, c->row_pos, c->cos_sin,
+                  c->kcache, c->vcache};
   for (void *p : ptrs) if (p) (void)hipFree(p);
   if (c->status_host) (void)hipHostFree(c->status_host);
+  if (c->seq_host) (void)hipHostFree(c->seq_host);
 }
 
 extern "C" pvf_status pvf_create(pvf_ctx **out, const pvf_model_cfg *m, const pvf_weights *w,
@@ -244,9 +254,11 @@ extern "C" int64_t pvf_workspace_bytes(const pvf_ctx *ctx) { return ctx ? ctx->w
 // forward
 // =========================================================================================
 // tokens: [*, T] rows addressed through seq_slot (NULL = identity).  Writes logits [S, R, V].
+// capture_spg > 0: the rotated keys and the values of every backbone canvas of the batch (slot
+// index divisible by capture_spg) are stored into the context's K/V cache after each layer.
 static pvf_status forward_impl(pvf_ctx *c, hipStream_t s, const int32_t *tokens,
                                const int32_t *seq_slot, int S, int T, const int32_t *row_pos,
-                               int R, void *logits) {
+                               int R, void *logits, int capture_spg = 0) {
   const pvf_model_cfg &m = c->model;
   const int d = m.d_model, H = m.n_heads, dh = d / H, ff = m.d_ff, dt = m.dtype;
   const int M = S * T;
@@ -267,6 +279,11 @@ static pvf_status forward_impl(pvf_ctx *c, hipStream_t s, const int32_t *tokens,
       ProfScope ps(c, s, PVF_PROF_ATTENTION, 4.0 * S * (double)T * T * d, 0.0);
       RUN(launch_rope_attention(c, s, dt, c->qkv, c->vt, c->att, S, T, H, dh, c->cos_sin));
     }
+    if (capture_spg > 0) {
+      const int64_t layer_off = (int64_t)l * T * d * c->esize, gstride = (int64_t)m.n_layers * T * d;
+      RUN(launch_kv_store(c, s, dt, c->qkv, nullptr, seq_slot, capture_spg, S, T, d, (char *)c->kcache + layer_off,
+                          (char *)c->vcache + layer_off, nullptr, gstride));
+    }
     RUN_GEMM(kEpiResidual, c->att, c->wo[l], c->h, c->h, M, d, d);
     RUN(launch_rmsnorm(c, s, dt, c->h, c->ffn_norm[l], c->xn, M, d, m.rms_eps));
     RUN_GEMM(kEpiSwiglu, c->xn, c->w_gate_up[l], c->act, nullptr, M, ff, d);
@@ -275,6 +292,47 @@ static pvf_status forward_impl(pvf_ctx *c, hipStream_t s, const int32_t *tokens,
   RUN(launch_gather_rows(c, s, dt, c->h, row_pos, S, T, R, d, c->hrows));
   RUN(launch_rmsnorm(c, s, dt, c->hrows, c->w.final_norm, c->hrows, S * R, d, m.rms_eps));
   RUN_GEMM(kEpiStore, c->hrows, c->w.out_head, logits, nullptr, S * R, m.vocab, d);
+#undef RUN_GEMM
+#undef RUN
+  return PVF_OK;
+}
+
+// Cached round (kv_cache): only the R window rows of each of the S canvases go through the
+// layers; keys / values outside the window come from the cache of the canvas' group.
+static pvf_status forward_window_impl(pvf_ctx *c, hipStream_t s, const pvf_decode_cfg &cfg, const pvf_state &state,
+                                      const int32_t *seq_slot, int S, const int32_t *row_pos, void *logits) {
+  const pvf_model_cfg &m = c->model;
+  const int d = m.d_model, H = m.n_heads, dh = d / H, ff = m.d_ff, dt = m.dtype;
+  const int T = cfg.prompt_len + cfg.gen_len, R = window_rows(cfg);
+  const int M = S * R;
+  pvf_status st;
+#define RUN(x) do { st = (x); if (st != PVF_OK) return st; } while (0)
+#define RUN_GEMM(epi, A, W, C, res, Mm, Nn, Kk)                                                   \
+  do {                                                                                            \
+    ProfScope ps(c, s, PVF_PROF_GEMM, 2.0 * (Mm) * (double)(Nn) * (Kk) * ((epi) == kEpiSwiglu ? 2 : 1),   \
+                 (double)c->esize * ((double)(Mm) * (Kk) + (double)(Nn) * (Kk) * ((epi) == kEpiSwiglu ? 2 : 1) + \
+                                     (double)(Mm) * (Nn) * ((epi) == kEpiResidual ? 2 : 1)));             \
+    RUN(launch_gemm(c, s, dt, epi, A, W, C, res, Mm, Nn, Kk));                                    \
+  } while (0)
+  RUN(launch_embed_rows(c, s, dt, c->w.embed, state.canvas, seq_slot, row_pos, M, R, T, d, m.vocab, c->h));
+  const int64_t gstride = (int64_t)m.n_layers * T * d;
+  for (int l = 0; l < m.n_layers; ++l) {
+    const int64_t layer_off = (int64_t)l * T * d * c->esize;
+    RUN(launch_rmsnorm(c, s, dt, c->h, c->attn_norm[l], c->xn, M, d, m.rms_eps));
+    RUN_GEMM(kEpiStore, c->xn, c->wqkv[l], c->qkv, nullptr, M, 3 * d, d);
+    {
+      ProfScope ps(c, s, PVF_PROF_ATTENTION, 4.0 * S * (double)R * T * d, 0.0);
+      RUN(launch_rope_rows(c, s, dt, c->qkv, row_pos, M, T, H, dh, c->cos_sin));
+      RUN(launch_attention_window(c, s, dt, c->qkv, (const char *)c->kcache + layer_off, (const char *)c->vcache + layer_off,
+                                  gstride, cfg, state, seq_slot, S, H, dh, c->att));
+    }
+    RUN_GEMM(kEpiResidual, c->att, c->wo[l], c->h, c->h, M, d, d);
+    RUN(launch_rmsnorm(c, s, dt, c->h, c->ffn_norm[l], c->xn, M, d, m.rms_eps));
+    RUN_GEMM(kEpiSwiglu, c->xn, c->w_gate_up[l], c->act, nullptr, M, ff, d);
+    RUN_GEMM(kEpiResidual, c->act, c->w_down[l], c->h, c->h, M, d, ff);
+  }
+  RUN(launch_rmsnorm(c, s, dt, c->h, c->w.final_norm, c->hrows, M, d, m.rms_eps));
+  RUN_GEMM(kEpiStore, c->hrows, c->w.out_head, logits, nullptr, M, m.vocab, d);
 #undef RUN_GEMM
 #undef RUN
   return PVF_OK;
@@ -377,8 +435,12 @@ static pvf_status check_round(pvf_ctx *ctx, int G, const uint32_t *plan_bitmap, 
   return PVF_OK;
 }
 
+static pvf_status round_cached_impl(pvf_ctx *ctx, hipStream_t s, int G, const uint32_t *plan_bitmap,
+                                    const pvf_decode_cfg &cfg, const pvf_state &state);
+
 static pvf_status round_impl(pvf_ctx *ctx, hipStream_t s, int G, const uint32_t *plan_bitmap,
                              const pvf_decode_cfg &cfg, const pvf_state &state, int n_seq) {
+  if (cfg.kv_cache) return round_cached_impl(ctx, s, G, plan_bitmap, cfg, state);
   const int T = cfg.prompt_len + cfg.gen_len, R = window_rows(cfg);
   const int all = G * (1 + cfg.K);
   if (n_seq <= 0 || n_seq > all) n_seq = all;
@@ -401,6 +463,80 @@ static pvf_status round_impl(pvf_ctx *ctx, hipStream_t s, int G, const uint32_t 
   return launch_stage2(ctx, s, G, ctx->model.vocab, ctx->model.mask_id, plan_bitmap, cfg, state);
 }
 
+// kv_cache round: groups whose active block differs from the block their cache was made for
+// (or that have no cache yet) get the full forward, which also refills their cache; the others
+// run the window forward.  The sequence list is built on the host from a read-back of the state.
+static pvf_status round_cached_impl(pvf_ctx *ctx, hipStream_t s, int G, const uint32_t *plan_bitmap,
+                                    const pvf_decode_cfg &cfg, const pvf_state &state) {
+  const pvf_model_cfg &m = ctx->model;
+  const int T = cfg.prompt_len + cfg.gen_len, R = window_rows(cfg), spg = 1 + cfg.K;
+  // cache memory
+  if (ctx->cache_G < G || ctx->cache_T != T) {
+    if (ctx->kcache) (void)hipFree(ctx->kcache);
+    if (ctx->vcache) (void)hipFree(ctx->vcache);
+    ctx->kcache = ctx->vcache = nullptr; ctx->cache_G = 0;
+    const size_t bytes = (size_t)G * m.n_layers * T * m.d_model * ctx->esize;
+    PVF_REQUIRE(ctx, hipMalloc(&ctx->kcache, bytes) == hipSuccess && hipMalloc(&ctx->vcache, bytes) == hipSuccess,
+                PVF_ENOMEM, "K/V cache: cannot allocate 2 x %zu bytes", bytes);
+    ctx->cache_G = G; ctx->cache_T = T;
+    ctx->cache_block.assign(G, -1);
+  }
+  if ((int)ctx->cache_block.size() < G) ctx->cache_block.resize(G, -1);
+  // state read-back and the two sequence lists
+  const int need = 3 * G + G * spg;
+  if (ctx->seq_host_cap < need) {
+    if (ctx->seq_host) (void)hipHostFree(ctx->seq_host);
+    ctx->seq_host = nullptr; ctx->seq_host_cap = 0;
+    PVF_HIP_CHECK(ctx, hipHostMalloc((void **)&ctx->seq_host, (size_t)need * sizeof(int32_t), hipHostMallocDefault));
+    ctx->seq_host_cap = need;
+  }
+  int32_t *h_done = ctx->seq_host, *h_nd = h_done + G, *h_ka = h_nd + G, *h_seq = h_ka + G;
+  PVF_HIP_CHECK(ctx, hipMemcpyAsync(h_done, state.done, G * sizeof(int32_t), hipMemcpyDeviceToHost, s));
+  PVF_HIP_CHECK(ctx, hipMemcpyAsync(h_nd, state.n_drafts, G * sizeof(int32_t), hipMemcpyDeviceToHost, s));
+  PVF_HIP_CHECK(ctx, hipMemcpyAsync(h_ka, state.k_active, G * sizeof(int32_t), hipMemcpyDeviceToHost, s));
+  PVF_HIP_CHECK(ctx, hipStreamSynchronize(s));
+  int n_full = 0, n_win = 0;
+  std::vector<int32_t> win;
+  for (int g = 0; g < G; ++g) {
+    if (h_done[g]) continue;
+    const int kt = h_nd[g] < 0 ? 0 : (h_nd[g] > cfg.K ? cfg.K : h_nd[g]);
+    const bool refresh = ctx->cache_block[g] != h_ka[g];
+    for (int j = 0; j <= kt; ++j) {
+      if (refresh) h_seq[n_full++] = g * spg + j;
+      else win.push_back(g * spg + j);
+    }
+    if (refresh) ctx->cache_block[g] = h_ka[g];
+  }
+  n_win = (int)win.size();
+  for (int i = 0; i < n_win; ++i) h_seq[n_full + i] = win[i];
+  const int n_seq = n_full + n_win;
+  if (n_seq == 0) return launch_stage2(ctx, s, G, m.vocab, m.mask_id, plan_bitmap, cfg, state);   // all done: reports an empty round
+  PVF_HIP_CHECK(ctx, hipMemcpyAsync(ctx->seq_slot, h_seq, n_seq * sizeof(int32_t), hipMemcpyHostToDevice, s));
+  pvf_status st = launch_fill_row_pos(ctx, s, cfg, state, ctx->seq_slot, n_seq, ctx->row_pos);
+  if (st != PVF_OK) return st;
+  if (n_full) {
+    st = forward_impl(ctx, s, state.canvas, ctx->seq_slot, n_full, T, ctx->row_pos, R, ctx->logits, spg);
+    if (st != PVF_OK) return st;
+  }
+  if (n_win) {
+    void *lg = (char *)ctx->logits + (size_t)n_full * R * m.vocab * ctx->esize;
+    st = forward_window_impl(ctx, s, cfg, state, ctx->seq_slot + n_full, n_win, ctx->row_pos + (size_t)n_full * R, lg);
+    if (st != PVF_OK) return st;
+  }
+  const RowFilter rf = make_filter(cfg, state, ctx->seq_slot);
+  {
+    ProfScope ps(ctx, s, PVF_PROF_STAGE1, 0.0, (double)n_seq * R * m.vocab * (double)ctx->esize);
+    st = launch_stage1(ctx, s, ctx->logits, m.dtype, (int64_t)n_seq * R, m.vocab, m.mask_id, cfg.logit_scale, rf,
+                       state.conf, state.tok);
+  }
+  if (st != PVF_OK) return st;
+  if (cfg.routes & PVF_ROUTES_CAL) {
+    st = launch_entropy(ctx, s, ctx->logits, m.dtype, (int64_t)n_seq * R, m.vocab, m.mask_id, cfg.logit_scale, rf, state.ent);
+    if (st != PVF_OK) return st;
+  }
+  return launch_stage2(ctx, s, G, m.vocab, m.mask_id, plan_bitmap, cfg, state);
+}
+
 extern "C" pvf_status pvf_round(pvf_ctx *ctx, void *stream, int32_t G, const uint32_t *plan_bitmap,
                                 const pvf_decode_cfg *cfg, const pvf_state *state, int32_t n_seq_host) {
   pvf_status st = check_round(ctx, G, plan_bitmap, cfg, state);
@@ -415,6 +551,7 @@ extern "C" pvf_status pvf_state_init(pvf_ctx *ctx, void *stream, const int32_t *
   if (st != PVF_OK) return st;
   if ((st = check_state(ctx, state, cfg)) != PVF_OK) return st;
   PVF_REQUIRE(ctx, G > 0 && (prompt || cfg->prompt_len == 0), PVF_EINVAL, "pvf_state_init: G=%d prompt=%p", G, (const void *)prompt);
+  ctx->cache_block.assign(ctx->cache_block.size(), -1);          // a fresh canvas has no valid K/V cache
   return launch_state_init(ctx, (hipStream_t)stream, prompt, G, ctx->model.mask_id, *cfg, *state);
 }
 
@@ -435,6 +572,7 @@ extern "C" pvf_status pvf_decode(pvf_ctx *ctx, void *stream, const int32_t *prom
   pvf_stats acc;
   memset(&acc, 0, sizeof(acc));
   const auto t0 = std::chrono::steady_clock::now();
+  ctx->cache_block.assign(ctx->cache_block.size(), -1);
   if ((st = launch_state_init(ctx, s, prompt, G, ctx->model.mask_id, *cfg, *state)) != PVF_OK) return st;
   int n_seq = G;                                  // first round: backbones only
   std::vector<int> prev_nd(G, 0);
