@@ -33,21 +33,43 @@ constexpr float kLog2e = 1.4426950408889634f;
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
+// Window mode (K/V-cached rounds): the queries are the R window rows of a canvas (qkv holds only
+// those rows, vt their key-contiguous values [seq][head][d][R]); a key inside the window
+// [w0, w0 + n_valid) is read from there, every other key from the cache of the canvas' group
+// (kc: rotated keys [T][d] row-major, vtc: values [head][d][T]).
+struct WinArgs {
+  const bf16_t *kc, *vtc;
+  int64_t group_stride;
+  const int32_t *seq_slot, *k_active;
+  int32_t slots_per_group, prompt_len, block_len, R;
+};
+
+template <bool WIN>
 __global__ void __launch_bounds__(256)
 attention_mfma_kernel(const bf16_t *__restrict__ qkv, const bf16_t *__restrict__ vt,
-                      bf16_t *__restrict__ out, int T, int H) {
+                      bf16_t *__restrict__ out, int T, int H, WinArgs wa) {
   __shared__ __attribute__((aligned(1024))) unsigned char lds[2 * kStage];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int fr = lane & 31, fh = lane >> 5;
   const int q0 = blockIdx.x * TQ, head = blockIdx.y, seq = blockIdx.z;
   const int d = H * DH;
-  const int64_t row0 = (int64_t)seq * T;
+  const int TQrows = WIN ? wa.R : T;                       // query rows per canvas in qkv / out
+  const int64_t row0 = (int64_t)seq * TQrows;
   const bf16_t *qb = qkv + row0 * 3 * d + (int64_t)head * DH;
   const bf16_t *kb = qb + d;
-  const bf16_t *vtb = vt + ((int64_t)seq * H + head) * DH * T;
+  const bf16_t *vtb = vt + ((int64_t)seq * H + head) * DH * TQrows;
+  int w0 = 0, w1 = 0;                                      // window = keys [w0, w1)
+  const bf16_t *kcb = nullptr, *vtcb = nullptr;
+  if (WIN) {
+    const int g = wa.seq_slot[seq] / wa.slots_per_group;
+    w0 = wa.prompt_len + wa.k_active[g] * wa.block_len;
+    w1 = w0 + min(wa.R, T - w0);
+    kcb = wa.kc + g * wa.group_stride + (int64_t)head * DH;
+    vtcb = wa.vtc + g * wa.group_stride + (int64_t)head * DH * T;
+  }
 
   // ---- Q fragments: "B" operand, column = query, k-chunk = 8 consecutive d ----
-  const int qrow = min(q0 + wave * 32 + fr, T - 1);
+  const int qrow = min(q0 + wave * 32 + fr, TQrows - 1);
   bf16x8 qf[8];
 #pragma unroll
   for (int ks = 0; ks < 8; ++ks)
@@ -57,20 +79,35 @@ attention_mfma_kernel(const bf16_t *__restrict__ qkv, const bf16_t *__restrict__
   // K tile: slot s = i*256 + tid -> key s/16, position s%16, chunk = position ^ (key & 15)
   // V^T tile: slot s -> d-row s/8, position s%8, chunk = position ^ ((row >> 1) & 7)
   const bf16_t *k_src[4], *v_src[4];
+  int k_key[4], k_col[4], v_row[4], v_key[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     const int s = i * 256 + tid;
     const int key = s >> 4, kc = (s & 15) ^ (key & 15);
     k_src[i] = kb + (int64_t)key * 3 * d + kc * 8;
+    k_key[i] = key; k_col[i] = kc * 8;
     const int vr = s >> 3, vc = (s & 7) ^ ((vr >> 1) & 7);
     v_src[i] = vtb + (int64_t)vr * T + vc * 8;
+    v_row[i] = vr; v_key[i] = vc * 8;
   }
   auto issue_loads = [&](int kt, int buf) {
     unsigned char *dst = lds + buf * kStage + wave * 1024;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      __builtin_amdgcn_global_load_lds((gptr_t *)(k_src[i] + (int64_t)kt * TK * 3 * d), (lptr_t *)(dst + i * 4096), 16, 0, 0);
-      __builtin_amdgcn_global_load_lds((gptr_t *)(v_src[i] + kt * TK), (lptr_t *)(dst + kKTile + i * 4096), 16, 0, 0);
+      const bf16_t *ks, *vs;
+      if (WIN) {
+        const int key = kt * TK + k_key[i];                // canvas position of this K row
+        ks = (key >= w0 && key < w1) ? kb + (int64_t)(key - w0) * 3 * d + k_col[i]
+                                     : kcb + (int64_t)key * d + k_col[i];
+        const int vk = kt * TK + v_key[i];                 // first of the 8 keys of this V^T chunk
+        vs = (vk >= w0 && vk < w1) ? vtb + (int64_t)v_row[i] * wa.R + (vk - w0)
+                                   : vtcb + (int64_t)v_row[i] * T + vk;
+      } else {
+        ks = k_src[i] + (int64_t)kt * TK * 3 * d;
+        vs = v_src[i] + kt * TK;
+      }
+      __builtin_amdgcn_global_load_lds((gptr_t *)ks, (lptr_t *)(dst + i * 4096), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((gptr_t *)vs, (lptr_t *)(dst + kKTile + i * 4096), 16, 0, 0);
     }
   };
 
@@ -156,7 +193,7 @@ attention_mfma_kernel(const bf16_t *__restrict__ qkv, const bf16_t *__restrict__
 
   // ---- out[q][head*128 + d]: lane holds 4 consecutive d per accumulator group ----
   const int q = q0 + wave * 32 + fr;
-  if (q < T) {
+  if (q < TQrows) {
     const float inv = 1.0f / l_run;
     bf16_t *orow = out + (row0 + q) * d + (int64_t)head * DH;
 #pragma unroll
@@ -204,7 +241,72 @@ rope_vt_kernel(bf16_t *__restrict__ qkv, bf16_t *__restrict__ vt, int T, int H,
   }
 }
 
+// Window rows: rotary embedding at the rows' own canvas positions (row_pos, -1 = padding row,
+// rotated like position T-1) and the key-contiguous copy vt[seq][head][d][r] of their values.
+// One block = 64 window rows of one (sequence, head).
+__global__ void __launch_bounds__(256)
+rope_vt_rows_kernel(bf16_t *__restrict__ qkv, bf16_t *__restrict__ vt, const int32_t *__restrict__ row_pos,
+                    int R, int T, int H, const float2 *__restrict__ cos_sin) {
+  __shared__ bf16_t tile[DH][64 + 2];
+  const int r0 = blockIdx.x * 64, head = blockIdx.y, seq = blockIdx.z;
+  const int d = H * DH;
+  const int tid = threadIdx.x;
+  bf16_t *base = qkv + ((int64_t)seq * R + r0) * 3 * d + (int64_t)head * DH;
+  for (int idx = tid; idx < 64 * 2 * 64; idx += 256) {
+    const int i = idx & 63, which = (idx >> 6) & 1, rr = idx >> 7;
+    int pos = row_pos[(int64_t)seq * R + r0 + rr];
+    if (pos < 0) pos = T - 1;
+    bf16_t *p = base + (int64_t)rr * 3 * d + which * d;
+    const float2 cs = cos_sin[(int64_t)pos * 64 + i];
+    const float a = (float)p[i], b = (float)p[i + 64];
+    p[i] = (bf16_t)(a * cs.x - b * cs.y);
+    p[i + 64] = (bf16_t)(b * cs.x + a * cs.y);
+  }
+  for (int idx = tid; idx < 64 * DH; idx += 256) {
+    const int dd = idx & 127, rr = idx >> 7;
+    tile[dd][rr] = base[(int64_t)rr * 3 * d + 2 * d + dd];
+  }
+  __syncthreads();
+  bf16_t *vb = vt + ((int64_t)seq * H + head) * DH * R + r0;
+  for (int idx = tid; idx < DH * 64; idx += 256) {
+    const int rr = idx & 63, dd = idx >> 6;
+    vb[(int64_t)dd * R + rr] = tile[dd][rr];
+  }
+}
+
 }  // namespace
+
+// Window attention on the matrix cores needs whole 64-row blocks of window rows and 8-key
+// chunks that lie entirely inside or outside the window.
+bool attention_window_mfma_supported(int dtype, int T, int d_head, int R, int block_len, int prompt_len) {
+  return dtype == PVF_BF16 && d_head == DH && T >= TK && T % TK == 0 && R % 64 == 0 && block_len % 8 == 0 &&
+         prompt_len % 8 == 0;
+}
+
+pvf_status launch_rope_vt_rows(pvf_ctx *ctx, hipStream_t s, void *qkv, void *vt, const int32_t *row_pos,
+                               int S, int R, int T, int n_heads, const float2 *cos_sin) {
+  if (S == 0) return PVF_OK;
+  const dim3 grid(R / 64, n_heads, S);
+  rope_vt_rows_kernel<<<grid, 256, 0, s>>>((bf16_t *)qkv, (bf16_t *)vt, row_pos, R, T, n_heads, cos_sin);
+  PVF_LAUNCH_CHECK(ctx, "rope_vt_rows");
+  return PVF_OK;
+}
+
+pvf_status launch_attention_window_mfma(pvf_ctx *ctx, hipStream_t s, const void *qkv_w, const void *vt_w,
+                                        const void *kc, const void *vtc, int64_t group_stride,
+                                        const int32_t *seq_slot, const int32_t *k_active, int slots_per_group,
+                                        int prompt_len, int block_len, int R, int S, int T, int n_heads,
+                                        void *out) {
+  if (S == 0) return PVF_OK;
+  WinArgs wa;
+  wa.kc = (const bf16_t *)kc; wa.vtc = (const bf16_t *)vtc; wa.group_stride = group_stride;
+  wa.seq_slot = seq_slot; wa.k_active = k_active; wa.slots_per_group = slots_per_group;
+  wa.prompt_len = prompt_len; wa.block_len = block_len; wa.R = R;
+  const dim3 grid((R + TQ - 1) / TQ, n_heads, S);
+  attention_mfma_kernel<true><<<grid, 256, 0, s>>>((const bf16_t *)qkv_w, (const bf16_t *)vt_w, (bf16_t *)out, T, n_heads, wa);
+  PVF_LAUNCH_CHECK(ctx, "attention_window_mfma");
+  return PVF_OK;
+}
 
 bool attention_mfma_supported(int dtype, int T, int d_head) {
   return dtype == PVF_BF16 && d_head == DH && T >= TK && T % TK == 0;
@@ -215,7 +317,7 @@ pvf_status launch_attention_mfma(pvf_ctx *ctx, hipStream_t s, const void *qkv, c
                                  void *out, int S, int T, int n_heads) {
   if (S == 0) return PVF_OK;
   const dim3 grid((T + TQ - 1) / TQ, n_heads, S);
-  attention_mfma_kernel<<<grid, 256, 0, s>>>((const bf16_t *)qkv, (const bf16_t *)vt, (bf16_t *)out, T, n_heads);
+  attention_mfma_kernel<false><<<grid, 256, 0, s>>>((const bf16_t *)qkv, (const bf16_t *)vt, (bf16_t *)out, T, n_heads, WinArgs{});
   PVF_LAUNCH_CHECK(ctx, "attention_mfma");
   return PVF_OK;
 }

@@ -27,6 +27,7 @@ struct pvf_ctx {
   // k / v thirds of the qkv buffer; cache_block[g] = active block the cache of group g is for
   void *kcache = nullptr, *vcache = nullptr;
   int cache_G = 0, cache_T = 0;
+  bool cache_vt = false;               // values cached key-contiguous [head][d_head][T] (MFMA window attention)
   std::vector<int> cache_block;
   int32_t *seq_host = nullptr;         // pinned staging of the round's sequence list
   int seq_host_cap = 0;
@@ -83,6 +84,10 @@ pvf_status launch_gemm_mfma(pvf_ctx *, hipStream_t, GemmEpilogue, const void *, 
 bool attention_mfma_supported(int dtype, int T, int d_head);
 pvf_status launch_attention_mfma(pvf_ctx *, hipStream_t, const void *, const void *, void *, int, int, int);
 pvf_status launch_rope_vt(pvf_ctx *, hipStream_t, void *, void *, int, int, int, const float2 *);
+bool attention_window_mfma_supported(int dtype, int T, int d_head, int R, int block_len, int prompt_len);
+pvf_status launch_rope_vt_rows(pvf_ctx *, hipStream_t, void *, void *, const int32_t *, int, int, int, int, const float2 *);
+pvf_status launch_attention_window_mfma(pvf_ctx *, hipStream_t, const void *, const void *, const void *, const void *,
+                                        int64_t, const int32_t *, const int32_t *, int, int, int, int, int, int, int, void *);
 
 static bool force_simple() {
   static const bool v = [] { const char *e = getenv("PVF_FORCE_SIMPLE"); return e && e[0] == '1'; }();
@@ -281,8 +286,9 @@ static pvf_status forward_impl(pvf_ctx *c, hipStream_t s, const int32_t *tokens,
     }
     if (capture_spg > 0) {
       const int64_t layer_off = (int64_t)l * T * d * c->esize, gstride = (int64_t)m.n_layers * T * d;
-      RUN(launch_kv_store(c, s, dt, c->qkv, nullptr, seq_slot, capture_spg, S, T, d, (char *)c->kcache + layer_off,
-                          (char *)c->vcache + layer_off, nullptr, gstride));
+      void *vl = (char *)c->vcache + layer_off;
+      RUN(launch_kv_store(c, s, dt, c->qkv, c->vt, seq_slot, capture_spg, S, T, d, (char *)c->kcache + layer_off,
+                          c->cache_vt ? nullptr : vl, c->cache_vt ? vl : nullptr, gstride));
     }
     RUN_GEMM(kEpiResidual, c->att, c->wo[l], c->h, c->h, M, d, d);
     RUN(launch_rmsnorm(c, s, dt, c->h, c->ffn_norm[l], c->xn, M, d, m.rms_eps));
@@ -322,9 +328,16 @@ static pvf_status forward_window_impl(pvf_ctx *c, hipStream_t s, const pvf_decod
     RUN_GEMM(kEpiStore, c->xn, c->wqkv[l], c->qkv, nullptr, M, 3 * d, d);
     {
       ProfScope ps(c, s, PVF_PROF_ATTENTION, 4.0 * S * (double)R * T * d, 0.0);
-      RUN(launch_rope_rows(c, s, dt, c->qkv, row_pos, M, T, H, dh, c->cos_sin));
-      RUN(launch_attention_window(c, s, dt, c->qkv, (const char *)c->kcache + layer_off, (const char *)c->vcache + layer_off,
-                                  gstride, cfg, state, seq_slot, S, H, dh, c->att));
+      if (c->cache_vt) {
+        RUN(launch_rope_vt_rows(c, s, c->qkv, c->vt, row_pos, S, R, T, H, c->cos_sin));
+        RUN(launch_attention_window_mfma(c, s, c->qkv, c->vt, (const char *)c->kcache + layer_off,
+                                         (const char *)c->vcache + layer_off, gstride, seq_slot, state.k_active,
+                                         1 + cfg.K, cfg.prompt_len, cfg.block_len, R, S, T, H, c->att));
+      } else {
+        RUN(launch_rope_rows(c, s, dt, c->qkv, row_pos, M, T, H, dh, c->cos_sin));
+        RUN(launch_attention_window(c, s, dt, c->qkv, (const char *)c->kcache + layer_off, (const char *)c->vcache + layer_off,
+                                    gstride, cfg, state, seq_slot, S, H, dh, c->att));
+      }
     }
     RUN_GEMM(kEpiResidual, c->att, c->wo[l], c->h, c->h, M, d, d);
     RUN(launch_rmsnorm(c, s, dt, c->h, c->ffn_norm[l], c->xn, M, d, m.rms_eps));
@@ -471,6 +484,12 @@ static pvf_status round_cached_impl(pvf_ctx *ctx, hipStream_t s, int G, const ui
   const pvf_model_cfg &m = ctx->model;
   const int T = cfg.prompt_len + cfg.gen_len, R = window_rows(cfg), spg = 1 + cfg.K;
   // cache memory
+  const bool want_vt = use_attention_mfma(m.dtype, T, m.d_model / m.n_heads) &&
+                       attention_window_mfma_supported(m.dtype, T, m.d_model / m.n_heads, R, cfg.block_len, cfg.prompt_len);
+  if (want_vt != ctx->cache_vt) {                          // the value layout changes: every cache is stale
+    ctx->cache_vt = want_vt;
+    ctx->cache_block.assign(ctx->cache_block.size(), -1);
+  }
   if (ctx->cache_G < G || ctx->cache_T != T) {
     if (ctx->kcache) (void)hipFree(ctx->kcache);
     if (ctx->vcache) (void)hipFree(ctx->vcache);

@@ -159,3 +159,48 @@ def test_bf16_cached_decode_completes_and_agrees_on_refresh_rounds():
         assert not (out == shape.mask_id).any() and stats.n_base + stats.n_plan + stats.n_ar == 2 * cfg.gen_len
         assert torch.equal(out[:, :64].cpu(), torch.from_numpy(prompts))
     assert np.array_equal(first[0][0], first[1][0]) and np.array_equal(first[0][1], first[1][1])
+
+
+def test_bf16_window_attention_on_matrix_cores_matches_oracle():
+    """d_head = 128, bf16, 64-row window: the cached round takes the MFMA window-attention path.
+    Round 1 (refresh) and round 2 (cached) are run on the GPU; the oracle repeats round 2 from the
+    GPU's own state after round 1, on the bf16-rounded weights.  bf16 activations move a
+    confidence by a few 1e-3 at this temperature, so confidences are compared within 2e-2 absolute
+    / 4e-3 on average, and top-1 tokens wherever the oracle's confidence is not tiny."""
+    from tests.gpu_util import oracle_state
+    shape = S.ModelShape(n_layers=2, d_model=256, n_heads=2, d_ff=512, vocab=4096, mask_id=4095, logit_scale=6.0)
+    w = S.make_weights(shape, seed=5)
+    wb = {k: (S.bf16_round(v) if k != "layers" else [{kk: S.bf16_round(vv) for kk, vv in lw.items()} for lw in v])
+          for k, v in w.items()}
+    mcfg = oracle_model_cfg(shape)
+    ctx = make_context(shape, to_device(wb, torch.bfloat16), max_seqs=10, max_T=192, max_rows=64)
+    cfg = B.DecodeCfg(block_len=32, prompt_len=64, gen_len=128, K=4, tau_high=0.9, tau_plan_lo=0.05, tau_plan_hi=0.6,
+                      tau_ar_lo=0.05, logit_scale=shape.logit_scale, kv_cache=1)
+    ocfg = oracle_decode_cfg(cfg)
+    G = 2
+    prompts = np.stack([S.make_prompt(15 + g, 64, shape.vocab, shape.mask_id) for g in range(G)])
+    plan = S.make_plan_vocab(1, 2000, shape.vocab, shape.mask_id)
+    bitmap = dev(S.plan_bitmap(plan, shape.vocab).view(np.int32), torch.int32)
+    st = B.State(G, cfg)
+    ctx.state_init(st, dev(prompts, torch.int32))
+    ctx.round(st, bitmap, 0)                                  # refresh: full forward, cache filled
+    torch.cuda.synchronize()
+    ost = [oracle_state(st, g) for g in range(G)]
+    assert all(not o.done and o.k_active == 0 for o in ost) and sum(o.drafts.n for o in ost) > 0
+    ctx.round(st, bitmap, 0)                                  # cached: window rows only
+    torch.cuda.synchronize()
+    worst, total, n, tok_ok, tok_n = 0.0, 0.0, 0, 0, 0
+    for g in range(G):
+        y0 = np.array(list(prompts[g]) + [shape.mask_id] * cfg.gen_len, dtype=np.int32)
+        _, cache = KV.forward_full(y0, wb, mcfg)              # what the refresh round cached: the initial canvas
+        cache.block = 0
+        conf, tok, _, refreshed = KV.cached_summaries(ost[g], cache, wb, mcfg, ocfg, cfg.logit_scale, shape.mask_id)
+        assert not refreshed
+        k = 1 + ost[g].drafts.n
+        gc, gt = st.conf[g].cpu().numpy()[:k], st.tok[g].cpu().numpy()[:k]
+        diff = np.abs(gc - conf)
+        worst, total, n = max(worst, float(diff.max())), total + float(diff.sum()), n + diff.size
+        sure = conf > 0.05
+        tok_ok += int((gt[sure] == tok[sure]).sum()); tok_n += int(sure.sum())
+    print(f"window MFMA attention: max |dconf| {worst:.2e}, mean {total / n:.2e}, tokens {tok_ok}/{tok_n}")
+    assert worst <= 2e-2 and total / n <= 4e-3 and tok_ok >= 0.98 * tok_n and tok_n > 20
