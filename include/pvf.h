@@ -89,12 +89,13 @@ typedef struct {
   int32_t n_sparse;     /* early cross-block revelation threshold N_s (App. A.4.1);     */
                         /* 0 = off: the working set is always the active block alone   */
   int32_t kv_cache;     /* 1 = block-level K/V cache (Sec. 5.1, "under KV cache"), used */
-                        /* by pvf_round / pvf_decode: a group gets the exact full       */
-                        /* forward in the first round and whenever its active block     */
-                        /* has changed, and that forward's per-layer rotated keys and   */
-                        /* values of the backbone canvas are kept; in all other rounds  */
-                        /* only the window rows of each canvas run through the layers   */
-                        /* and attend to the cached keys / values outside the window.   */
+                        /* by pvf_round / pvf_decode: a group's backbone canvas gets    */
+                        /* the exact full forward in the first round and whenever its   */
+                        /* active block has changed, and that forward's per-layer       */
+                        /* rotated keys and values are kept; every other canvas (all    */
+                        /* drafts; the backbone in the other rounds) runs only its      */
+                        /* window rows through the layers, attending to the cached      */
+                        /* keys / values outside the window.                            */
                         /* 0 = every round is a full forward (exact)                    */
 } pvf_decode_cfg;
 

@@ -9,9 +9,10 @@ the positions of the working window.  The paper gives no further detail, so the 
 fixed here (readings):
 
   K1  refresh: in the first round, and in every round whose active block differs from the
-      block the cache was made for, every canvas of the batch gets the exact full forward;
-      the per-layer rotated keys and the values of the BACKBONE canvas become the cache.
-  K2  other rounds: for each canvas of the batch only the window rows (the rows whose logits
+      block the cache was made for, the BACKBONE canvas gets the exact full forward; its
+      per-layer rotated keys and values become the cache.  The drafts of such a round are
+      forwarded like in any other round (K2), against the cache just made.
+  K2  otherwise: for a canvas of the batch only the window rows (the rows whose logits
       the decision step reads: 2 blocks from the active block, 4 with early cross-block
       revelation, cut at the end of the canvas) run through the layers.  In every layer their
       queries attend to all T positions: keys / values of window positions are the ones just
@@ -129,12 +130,10 @@ def cached_summaries(state: O.State, cache: Optional[KVCache], weights: Dict, mc
     tok = np.full((len(X), cfg.window_rows), -1, np.int32)
     refresh = force_refresh or cache is None or cache.block != state.k_active
     for j, x in enumerate(X):
-        if refresh:
-            lg, c = forward_full(x, weights, mcfg)
+        if refresh and j == 0:
+            lg, cache = forward_full(x, weights, mcfg)
             lg = lg[wp[ok]]
-            if j == 0:
-                cache = c
-                cache.block = state.k_active
+            cache.block = state.k_active
         else:
             lg = forward_window(x, wp[ok], cache, weights, mcfg)
         conf[j, ok], tok[j, ok] = O.stage1(lg, scale, mask_id)

@@ -476,9 +476,9 @@ static pvf_status round_impl(pvf_ctx *ctx, hipStream_t s, int G, const uint32_t 
   return launch_stage2(ctx, s, G, ctx->model.vocab, ctx->model.mask_id, plan_bitmap, cfg, state);
 }
 
-// kv_cache round: groups whose active block differs from the block their cache was made for
-// (or that have no cache yet) get the full forward, which also refills their cache; the others
-// run the window forward.  The sequence list is built on the host from a read-back of the state.
+// kv_cache round: the backbone of a group whose active block differs from the block its cache was
+// made for (or that has no cache yet) gets the full forward, which also refills the cache; every
+// other canvas runs the window forward (after the full one, so it sees the fresh cache).  The sequence list is built on the host from a read-back of the state.
 static pvf_status round_cached_impl(pvf_ctx *ctx, hipStream_t s, int G, const uint32_t *plan_bitmap,
                                     const pvf_decode_cfg &cfg, const pvf_state &state) {
   const pvf_model_cfg &m = ctx->model;
@@ -520,8 +520,8 @@ static pvf_status round_cached_impl(pvf_ctx *ctx, hipStream_t s, int G, const ui
     if (h_done[g]) continue;
     const int kt = h_nd[g] < 0 ? 0 : (h_nd[g] > cfg.K ? cfg.K : h_nd[g]);
     const bool refresh = ctx->cache_block[g] != h_ka[g];
-    for (int j = 0; j <= kt; ++j) {
-      if (refresh) h_seq[n_full++] = g * spg + j;
+    for (int j = 0; j <= kt; ++j) {                         // only the backbone of a refreshing group is forwarded in full
+      if (refresh && j == 0) h_seq[n_full++] = g * spg + j;
       else win.push_back(g * spg + j);
     }
     if (refresh) ctx->cache_block[g] = h_ka[g];

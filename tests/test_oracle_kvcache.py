@@ -121,15 +121,35 @@ def test_window_forward_matches_loop_definition_and_is_stale_outside():
 
 @pytest.mark.parametrize("seed", range(3))
 def test_refresh_every_round_is_plain_decoding(seed):
+    """With a refresh in every round the backbone always gets the exact forward: without drafts
+    that is plain threshold decoding; with drafts the backbone's own summaries are still exact
+    (the drafts, forwarded against the cache, are the only approximation)."""
     w, cfg = model(seed=10 + seed)
-    dcfg = O.DecodeCfg(block_len=4, prompt_len=6, gen_len=12, tau_high=0.6, tau_plan_lo=0.1, tau_plan_hi=0.5,
-                       tau_ar_lo=0.2, K=2)
     plan = list(range(0, 40, 3))
     prompt = S.make_prompt(seed, 6, SHAPE.vocab, SHAPE.mask_id)
     fn = lambda c: O.forward(c, w, cfg)
-    plain = O.decode(prompt, fn, dcfg, SHAPE.logit_scale, SHAPE.mask_id, plan)
-    forced = KV.decode_cached(prompt, w, cfg, dcfg, SHAPE.logit_scale, SHAPE.mask_id, plan, force_refresh=True)
+    d0 = O.DecodeCfg(block_len=4, prompt_len=6, gen_len=12, tau_high=0.6, tau_plan_lo=0.1, tau_plan_hi=0.5, K=0)
+    plain = O.decode(prompt, fn, d0, SHAPE.logit_scale, SHAPE.mask_id, plan)
+    forced = KV.decode_cached(prompt, w, cfg, d0, SHAPE.logit_scale, SHAPE.mask_id, plan, force_refresh=True)
     assert np.array_equal(forced.tokens, plain.tokens) and forced.nfe == plain.nfe == forced.n_refresh
+    d2 = O.DecodeCfg(block_len=4, prompt_len=6, gen_len=12, tau_high=0.6, tau_plan_lo=0.1, tau_plan_hi=0.5,
+                     tau_ar_lo=0.2, K=2)
+    st, cache = O.initial_state(prompt, d2, SHAPE.mask_id), None
+    for _ in range(4):
+        if st.done:
+            break
+        conf, tok, cache, refreshed = KV.cached_summaries(st, cache, w, cfg, d2, SHAPE.logit_scale, SHAPE.mask_id, True)
+        exact_c, exact_t = O.summaries(st, fn, d2, SHAPE.logit_scale, SHAPE.mask_id)
+        assert refreshed and np.array_equal(tok[0], exact_t[0])
+        np.testing.assert_allclose(conf[0], exact_c[0], rtol=1e-5)
+        # a draft is forwarded on its window rows against the backbone's fresh cache
+        if st.drafts.n:
+            X = O.branch_canvases(st.y, st.drafts)
+            wp = O.window_positions(d2, st.k_active); ok = wp < d2.T
+            lg = KV.forward_window(X[1], wp[ok], cache, w, cfg)
+            c1, t1 = O.stage1(lg, SHAPE.logit_scale, SHAPE.mask_id)
+            assert np.array_equal(tok[1][ok], t1) and np.array_equal(conf[1][ok], c1)
+        st, _ = O.decide(st, conf, tok, d2, SHAPE.mask_id, plan)
 
 
 @pytest.mark.parametrize("seed,ns", [(0, 0), (1, 0), (2, 2)])
