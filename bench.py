@@ -48,6 +48,8 @@ def parse():
     ap.add_argument("--no-epilogue", action="store_true")
     ap.add_argument("--no-decodes", action="store_true",
                     help="skip the two whole decodes (PVF and K = 0) that only feed the tokens-per-forward fields")
+    ap.add_argument("--all-configs", action="store_true",
+                    help="also time one full-batch forward of the 9 x 1280 and 80 x 1024 configurations")
     ap.add_argument("--pmc-reference", action="store_true",
                     help="also run a plain device-to-device copy of 256 MiB (reference for scaling "
                          "rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
@@ -154,6 +156,22 @@ def cpu_baseline(dims, T, R, canv_per_round, tpf, threads):
             "seconds_per_round_extrapolated": round(t_round, 2)}
 
 
+def forward_full_batch(ctx, W, dims, S, T, R, torch, iters):
+    """One forward over S full canvases (every draft slot live): ms, TFLOP/s and share of the bf16 peak."""
+    tokens = W.random_prompts(S, T, dims["vocab"], dims["mask_id"], seed=7)
+    rows = torch.arange(T - R, T, dtype=torch.int32, device="cuda")[None].repeat(S, 1).contiguous()
+    for _ in range(2):
+        ctx.forward(tokens, rows)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(iters):
+        ctx.forward(tokens, rows)
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / iters
+    fl = W.flops_per_round(dims, S, T, R)
+    return {"ms": round(dt * 1e3, 2), "tflops": round(fl / dt / 1e12, 1), "frac_of_bf16_peak": round(fl / dt / 1e12 / PEAK_BF16_TFLOPS, 4)}
+
+
 def main():
     a = parse()
     if a.gpus != 1:
@@ -222,6 +240,27 @@ def main():
         res["pvf_vs_threshold"] = {"tpf_ratio": round(s_thr.rounds / s_pvf.rounds, 3),
                                    "tokens_per_s_ratio": round(res["pvf_decode"]["tokens_per_s"] /
                                                                res["threshold_decoding"]["tokens_per_s"], 3)}
+    if s_pvf is not None:
+        # the same two decodes with the block-level K/V cache (the setting of the paper's tokens/s; approximate)
+        kv = {}
+        for name, k in (("pvf", K), ("threshold", 0)):
+            c = B.DecodeCfg(block_len=bl, prompt_len=P, gen_len=Gn, K=k, tau_high=0.9, logit_scale=LOGIT_SCALE, kv_cache=1)
+            ctx.decode(B.State(1, c), prompt, bitmap)                       # warm-up (cache allocation, tile shapes)
+            o, s_kv = ctx.decode(B.State(1, c), prompt, bitmap)
+            assert int((o == dims["mask_id"]).sum()) == 0
+            kv[name] = {"nfe": s_kv.rounds, "tokens_per_s": round(Gn / s_kv.ms_total * 1e3, 2),
+                        "ms_per_round": round(s_kv.ms_total / s_kv.rounds, 3), "canvases_forwarded": s_kv.seq_forwards}
+        res["kv_cache_decode"] = kv
+    res["forward_full_batch"] = {"c3_5x512": forward_full_batch(ctx, W, dims, 1 + K, T, R, torch, 10)}
+    if a.all_configs:
+        del ctx
+        torch.cuda.empty_cache()
+        for name, (S_, T_, R_) in (("c4_9x1280", (9, 1280, 128)), ("c5_80x1024", (80, 1024, 64))):
+            c2 = W.make_context(dims, weights, max_seqs=S_, max_T=T_, max_rows=R_)
+            res["forward_full_batch"][name] = forward_full_batch(c2, W, dims, S_, T_, R_, torch, 3)
+            del c2
+            torch.cuda.empty_cache()
+        ctx = None
     if not a.no_epilogue:
         res["roofline_epilogue"] = epilogue_roofline(B, torch)
     if not a.no_cpu_baseline:
