@@ -31,7 +31,6 @@ namespace {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
-constexpr int kGroupM = 8;
 
 typedef __attribute__((address_space(1))) const void gptr_t;
 typedef __attribute__((address_space(3))) void lptr_t;
@@ -72,7 +71,7 @@ __attribute__((amdgpu_waves_per_eu(waves_per_simd(kStages * (BM + BN) * BK * 2, 
                                    waves_per_simd(kStages * (BM + BN) * BK * 2, WM * WN))))
 gemm_bf16_mfma_kernel(const bf16_t *__restrict__ A, const bf16_t *__restrict__ W,
                       bf16_t *__restrict__ C, const bf16_t *__restrict__ Res, int M, int N_out,
-                      int K, int tiles_m, int tiles_n) {
+                      int K, int tiles_m, int tiles_n, int group_m) {
   constexpr int kThreads = 64 * WM * WN;
   constexpr int MT = BM / (32 * WM), NT = BN / (32 * WN);  // MFMA tiles per wave in each direction
   constexpr int kATile = BM * BK * 2, kWTile = BN * BK * 2, kStage = kATile + kWTile;
@@ -94,11 +93,11 @@ gemm_bf16_mfma_kernel(const bf16_t *__restrict__ A, const bf16_t *__restrict__ W
   const int chunk = (total + 7) >> 3;
   const int L = (blockIdx.x & 7) * chunk + (blockIdx.x >> 3);
   if (L >= total) return;
-  const int band = L / (kGroupM * tiles_n);
-  const int within = L - band * (kGroupM * tiles_n);
-  const int band_rows = min(kGroupM, tiles_m - band * kGroupM);
+  const int band = L / (group_m * tiles_n);
+  const int within = L - band * (group_m * tiles_n);
+  const int band_rows = min(group_m, tiles_m - band * group_m);
   const int tile_n = within / band_rows;
-  const int tile_m = band * kGroupM + (within - tile_n * band_rows);
+  const int tile_m = band * group_m + (within - tile_n * band_rows);
   const int m0 = tile_m * BM;
 
   // ---- global -> LDS: thread tid fills 16-byte slot (i*kThreads + tid) of an operand tile:
@@ -308,8 +307,12 @@ pvf_status run(pvf_ctx *ctx, hipStream_t s, const void *A, const void *W, void *
   const int tiles_n = (EPI == kEpiSwiglu) ? N_out / (BN / 2) : N_out / BN;
   const int total = tiles_m * tiles_n;
   const int grid = 8 * ((total + 7) / 8);
+  // bands of at most 8 tile rows, all of (nearly) the same height: the 32 workgroups that run
+  // together on an XCD then cover a patch close to 8 x 4 tiles in every band
+  const int n_bands = (tiles_m + 7) / 8;
+  const int group_m = (tiles_m + n_bands - 1) / n_bands;
   gemm_bf16_mfma_kernel<EPI, BM, BN, BK, ST, WM, WN><<<grid, 64 * WM * WN, kLdsBytes, s>>>(
-      (const bf16_t *)A, (const bf16_t *)W, (bf16_t *)C, (const bf16_t *)Res, M, N_out, K, tiles_m, tiles_n);
+      (const bf16_t *)A, (const bf16_t *)W, (bf16_t *)C, (const bf16_t *)Res, M, N_out, K, tiles_m, tiles_n, group_m);
   PVF_LAUNCH_CHECK(ctx, "gemm_mfma");
   return PVF_OK;
 }
