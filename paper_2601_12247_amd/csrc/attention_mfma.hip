@@ -45,7 +45,7 @@ struct WinArgs {
 };
 
 template <bool WIN>
-__global__ void __launch_bounds__(256)
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
 attention_mfma_kernel(const bf16_t *__restrict__ qkv, const bf16_t *__restrict__ vt,
                       bf16_t *__restrict__ out, int T, int H, WinArgs wa) {
   __shared__ __attribute__((aligned(1024))) unsigned char lds[2 * kStage];
