@@ -35,7 +35,7 @@ LOGIT_SCALE = 12.0             # calibrated once: K=0 decoding of this model lan
 # HBM-side bytes per launch (L2 fills + write-backs) from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE passes over
 # this script, scaled by what the counters read for a plain 256 MiB copy; the passes and the arithmetic are in
 # profiles/bench_c3_llada8b_pmc_hbm_traffic.txt
-TRAFFIC_GEMM = 457.6e6         # mean over the GEMM launches of the timed mix (algorithmic: 178.6e6)
+TRAFFIC_GEMM = 444.1e6         # mean over the GEMM launches of the timed mix (algorithmic: 178.6e6)
 TRAFFIC_STAGE1 = 518.6e6       # [2048, 126464] bf16 logits (algorithmic: 518.0e6)
 
 
@@ -47,7 +47,8 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-epilogue", action="store_true")
     ap.add_argument("--no-decodes", action="store_true",
-                    help="skip the two whole decodes (PVF and K = 0) that only feed the tokens-per-forward fields")
+                    help="only the timed rounds and the stage-1 measurement: skip the whole decodes (PVF, K = 0, with and "
+                         "without K/V cache) and the full-batch forward timing; used for profiling runs")
     ap.add_argument("--all-configs", action="store_true",
                     help="also time one full-batch forward of the 9 x 1280 and 80 x 1024 configurations")
     ap.add_argument("--pmc-reference", action="store_true",
@@ -251,8 +252,9 @@ def main():
             kv[name] = {"nfe": s_kv.rounds, "tokens_per_s": round(Gn / s_kv.ms_total * 1e3, 2),
                         "ms_per_round": round(s_kv.ms_total / s_kv.rounds, 3), "canvases_forwarded": s_kv.seq_forwards}
         res["kv_cache_decode"] = kv
-    res["forward_full_batch"] = {"c3_5x512": forward_full_batch(ctx, W, dims, 1 + K, T, R, torch, 10)}
-    if a.all_configs:
+    if not a.no_decodes:
+        res["forward_full_batch"] = {"c3_5x512": forward_full_batch(ctx, W, dims, 1 + K, T, R, torch, 10)}
+    if a.all_configs and not a.no_decodes:
         del ctx
         torch.cuda.empty_cache()
         for name, (S_, T_, R_) in (("c4_9x1280", (9, 1280, 128)), ("c5_80x1024", (80, 1024, 64))):

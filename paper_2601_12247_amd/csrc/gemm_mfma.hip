@@ -351,7 +351,9 @@ int pick_config(GemmEpilogue epi, int M, int N, int K) {
   // Few rows: the launch streams the weight matrix once and is bound by HBM, not by the MFMAs.
   // Many small workgroups with deep LDS rings keep more bytes in flight (measured on the layer
   // shapes: 3.2x faster than the large tiles at M = 64, 2x at M = 320).
-  if (forced < 0 && M <= 384 && K % 64 == 0) {
+  // The output head (N = vocabulary) has enough tiles to fill the chip at any M > 64 and goes by the
+  // cost model below.
+  if (forced < 0 && M <= 384 && K % 64 == 0 && (M <= 64 || N <= 32768)) {
     if (epi != kEpiSwiglu && M <= 128 && N % 64 == 0) return 6;
     if (N % (epi == kEpiSwiglu ? 64 : 128) == 0) return 7;
   }
