@@ -54,7 +54,7 @@ typedef enum {
 
 enum { PVF_F32 = 0, PVF_BF16 = 1 };
 enum { PVF_ROUTE_NONE = 0, PVF_ROUTE_PLAN = 1, PVF_ROUTE_AR = 2, PVF_ROUTE_CAL = 3 };
-enum { PVF_ROUTES_PLAN = 1, PVF_ROUTES_AR = 2, PVF_ROUTES_CAL = 4 };
+enum { PVF_ROUTES_PLAN = 1, PVF_ROUTES_AR = 2, PVF_ROUTES_CAL = 4, PVF_ROUTES_XRANDOM = 8, PVF_ROUTES_XPLANNING = 16 };
 
 typedef struct pvf_ctx pvf_ctx;
 
@@ -85,9 +85,19 @@ typedef struct {
                         /* threshold decoding whose drafts are the non-base masks with  */
                         /* confidence in [tau_plan_lo, tau_plan_hi) (the calibration    */
                         /* band, any token, the K most confident); they are measured    */
-                        /* (A_j, Delta H_j) into the token statistics, never committed  */
+                        /* (A_j, Delta H_j) into the token statistics, never committed. */
+                        /* PVF_ROUTES_XRANDOM / PVF_ROUTES_XPLANNING alone = the two    */
+                        /* ablation decoders of App. A.3.1: threshold decoding plus ONE */
+                        /* extra commit per round among the remaining masks whose       */
+                        /* confidence lies in the closed bin [tau_plan_lo, tau_plan_hi],*/
+                        /* uniformly at random (XPLANNING: among those whose token is a */
+                        /* planning token, if any).  The pick is the (u mod count)-th   */
+                        /* eligible position in canvas order, u = SplitMix64 step of    */
+                        /* seed * 2^32 + (group & 0xFFF) * 2^20 + masked positions left */
+                        /* on the canvas; n_commit[.][1] counts these commits           */
   int32_t n_sparse;     /* early cross-block revelation threshold N_s (App. A.4.1);     */
                         /* 0 = off: the working set is always the active block alone   */
+  uint32_t seed;        /* seed of the ablation decoders' generator                    */
   int32_t kv_cache;     /* 1 = block-level K/V cache (Sec. 5.1, "under KV cache"), used */
                         /* by pvf_round / pvf_decode: a group's backbone canvas gets    */
                         /* the exact full forward in the first round and whenever its   */

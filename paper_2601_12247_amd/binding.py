@@ -17,7 +17,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libpvf.so")
 
 PVF_F32, PVF_BF16 = 0, 1
-PVF_ROUTES_PLAN, PVF_ROUTES_AR, PVF_ROUTES_CAL = 1, 2, 4
+PVF_ROUTES_PLAN, PVF_ROUTES_AR, PVF_ROUTES_CAL, PVF_ROUTES_XRANDOM, PVF_ROUTES_XPLANNING = 1, 2, 4, 8, 16
 PVF_ROUTE_NONE, PVF_ROUTE_PLAN, PVF_ROUTE_AR, PVF_ROUTE_CAL = 0, 1, 2, 3
 ROUTE_NONE, ROUTE_PLAN, ROUTE_AR = 0, 1, 2
 MAX_K = 16
@@ -48,7 +48,7 @@ class DecodeCfgC(C.Structure):
     _fields_ = [("tau_high", C.c_float), ("tau_plan_lo", C.c_float), ("tau_plan_hi", C.c_float),
                 ("tau_ar_lo", C.c_float), ("logit_scale", C.c_float), ("K", C.c_int32),
                 ("block_len", C.c_int32), ("prompt_len", C.c_int32), ("gen_len", C.c_int32),
-                ("routes", C.c_int32), ("n_sparse", C.c_int32), ("kv_cache", C.c_int32)]
+                ("routes", C.c_int32), ("n_sparse", C.c_int32), ("seed", C.c_uint32), ("kv_cache", C.c_int32)]
 
 
 class WeightsC(C.Structure):
@@ -171,6 +171,7 @@ class DecodeCfg:
     K: int = 3
     routes: int = 3
     n_sparse: int = 0
+    seed: int = 0
     kv_cache: int = 0
 
     @property
@@ -184,7 +185,7 @@ class DecodeCfg:
     def c(self) -> DecodeCfgC:
         return DecodeCfgC(self.tau_high, self.tau_plan_lo, self.tau_plan_hi, self.tau_ar_lo,
                           self.logit_scale, self.K, self.block_len, self.prompt_len, self.gen_len,
-                          self.routes, self.n_sparse, self.kv_cache)
+                          self.routes, self.n_sparse, self.seed, self.kv_cache)
 
 
 class State:

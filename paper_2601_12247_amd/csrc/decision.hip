@@ -32,6 +32,14 @@ struct Stage2Args {
 };
 
 constexpr int kStage2Threads = 256;
+
+// SplitMix64 step (Steele, Lea, Flood 2014): the counter-based generator of the ablation decoders
+__device__ __forceinline__ uint64_t splitmix64(uint64_t z) {
+  z += 0x9E3779B97F4A7C15ull;
+  z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+  z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+  return z ^ (z >> 31);
+}
 constexpr int kMaxWinBlocks = 4;
 
 // Dynamic LDS layout: conf[(1+K)*R] | tok[(1+K)*R] | x[R] | flag[2*block_len]
@@ -215,14 +223,40 @@ __global__ void __launch_bounds__(kStage2Threads) stage2_kernel(Stage2Args a) {
     }
     __syncthreads();
     for (int i = tid; i < plen; i += nth) if (s_flag[i] == 2) xb[i] = tw[i];
-    const int n_left = s_cnt[3] - s_cnt[1];      // masks left in the proposing set
     if (tid == 0) {
       ncommit[0] = s_cnt[1];
-      int total = masks_beyond;
+      int total = masks_beyond;                  // masked positions of the whole canvas before this step's commits
       for (int b = 0; b < nwb; ++b) total += s_blk[b];
+      int extra = 0;
+      if (a.cfg.routes & (PVF_ROUTES_XRANDOM | PVF_ROUTES_XPLANNING)) {
+        // Ablation decoders (App. A.3.1): one more commit among the remaining masks whose
+        // confidence lies in the closed bin; planning tokens first if asked for.
+        int n_el = 0, n_pl = 0;
+        for (int i = 0; i < plen; ++i) {
+          if (s_flag[i] != 1 || !(cw[i] >= a.cfg.tau_plan_lo && cw[i] <= a.cfg.tau_plan_hi)) continue;
+          ++n_el;
+          const int t = tw[i];
+          if (t >= 0 && t < a.vocab && ((a.plan_bitmap[t >> 5] >> (t & 31)) & 1u)) ++n_pl;
+        }
+        const bool use_plan = (a.cfg.routes & PVF_ROUTES_XPLANNING) && n_pl > 0;
+        const int n_pool = use_plan ? n_pl : n_el;
+        if (n_pool > 0) {
+          const uint64_t key = ((uint64_t)a.cfg.seed << 32) + ((uint64_t)(g & 0xFFF) << 20) + (uint64_t)(total & 0xFFFFF);
+          int pick = (int)(splitmix64(key) % (uint64_t)n_pool);
+          for (int i = 0; i < plen; ++i) {
+            if (s_flag[i] != 1 || !(cw[i] >= a.cfg.tau_plan_lo && cw[i] <= a.cfg.tau_plan_hi)) continue;
+            const int t = tw[i];
+            if (use_plan && !(t >= 0 && t < a.vocab && ((a.plan_bitmap[t >> 5] >> (t & 31)) & 1u))) continue;
+            if (pick-- == 0) { s_flag[i] = 2; xb[i] = t; extra = 1; break; }
+          }
+        }
+        ncommit[1] = extra;                      // reported in the planning slot of n_commit
+      }
+      s_cnt[1] += extra;
       if (total - s_cnt[1] == 0) s_done = 1;     // nothing left anywhere: no further forward
     }
     __syncthreads();
+    const int n_left = s_cnt[3] - s_cnt[1];      // masks left in the proposing set
 
     if (!s_done && K > 0 && n_left > 0) {
       // planning candidates: non-base masks whose top-1 is a planning token, confidence in the band

@@ -129,7 +129,10 @@ static pvf_status check_decode_cfg(pvf_ctx *ctx, const pvf_decode_cfg *c, int vo
   PVF_REQUIRE(ctx, c->tau_plan_lo <= c->tau_plan_hi && c->tau_plan_hi <= c->tau_high, PVF_EINVAL,
               "need tau_plan_lo <= tau_plan_hi <= tau_high (%g, %g, %g)", c->tau_plan_lo, c->tau_plan_hi, c->tau_high);
   PVF_REQUIRE(ctx, c->logit_scale > 0.f && std::isfinite(c->logit_scale), PVF_EINVAL, "logit_scale=%g must be positive", c->logit_scale);
-  PVF_REQUIRE(ctx, (c->routes & ~7) == 0, PVF_EINVAL, "routes=%d has unknown bits", c->routes);
+  PVF_REQUIRE(ctx, (c->routes & ~31) == 0, PVF_EINVAL, "routes=%d has unknown bits", c->routes);
+  PVF_REQUIRE(ctx, !(c->routes & (PVF_ROUTES_XRANDOM | PVF_ROUTES_XPLANNING)) || c->routes == PVF_ROUTES_XRANDOM ||
+                  c->routes == PVF_ROUTES_XPLANNING, PVF_EINVAL,
+              "routes=%d: an ablation decoder excludes every other route", c->routes);
   PVF_REQUIRE(ctx, !(c->routes & PVF_ROUTES_CAL) || c->routes == PVF_ROUTES_CAL, PVF_EINVAL,
               "routes=%d: the calibration trajectory excludes the planning and AR routes", c->routes);
   PVF_REQUIRE(ctx, c->n_sparse >= 0, PVF_EINVAL, "n_sparse=%d must be >= 0", c->n_sparse);

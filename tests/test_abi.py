@@ -24,7 +24,7 @@ def test_library_exports_every_declared_symbol():
 
 def test_struct_layouts_match_header_sizes():
     assert ctypes.sizeof(B.ModelCfgC) == 9 * 4
-    assert ctypes.sizeof(B.DecodeCfgC) == 12 * 4
+    assert ctypes.sizeof(B.DecodeCfgC) == 13 * 4
     assert ctypes.sizeof(B.StateC) == 19 * 8
     assert ctypes.sizeof(B.WeightsC) == 9 * 8
     assert ctypes.sizeof(B.StatsC) == 2 * 4 + 5 * 8 + 8
