@@ -318,14 +318,15 @@ pvf_status run(pvf_ctx *ctx, hipStream_t s, const void *A, const void *W, void *
 }
 
 struct TileCfg { int bm, bn, bk, stages; double eff; };
-constexpr int kNumCfg = 8;
+constexpr int kNumCfg = 9;
 constexpr TileCfg kCfg[kNumCfg] = {
     {256, 256, 32, 4, 1.00},   // 8 waves
     {128, 256, 64, 3, 0.85}, {256, 128, 64, 3, 0.85}, {128, 128, 64, 4, 0.80},
     {256, 256, 32, 4, 0.0},    // shape 0 with 4 waves (only when forced)
     {192, 256, 32, 4, 0.97},   // fills the chip when M / 256 leaves many CUs idle
     {64, 64, 64, 5, 0.0},      // few rows (window forward of the K/V-cached rounds): the GEMM streams the weights,
-    {64, 128, 64, 3, 0.0}};    // so many small workgroups with deep rings; chosen by pick_config for M <= 320
+    {64, 128, 64, 3, 0.0},     // so many small workgroups with deep rings; chosen by pick_config for M <= 320
+    {160, 256, 64, 3, 0.90}};  // 2560 rows = 16 tile rows: with N = 4096 exactly one tile per CU
 
 template <int EPI>
 pvf_status run_cfg(pvf_ctx *ctx, hipStream_t s, int cfg, const void *A, const void *W, void *C,
@@ -338,7 +339,8 @@ pvf_status run_cfg(pvf_ctx *ctx, hipStream_t s, int cfg, const void *A, const vo
     case 4: return run<EPI, 256, 256, 32, 4, 2, 2>(ctx, s, A, W, C, Res, M, N, K);
     case 5: return run<EPI, 192, 256, 32, 4, 2, 2>(ctx, s, A, W, C, Res, M, N, K);
     case 6: if constexpr (EPI != kEpiSwiglu) return run<EPI, 64, 64, 64, 5, 2, 2>(ctx, s, A, W, C, Res, M, N, K);
-    default: return run<EPI, 64, 128, 64, 3, 2, 2>(ctx, s, A, W, C, Res, M, N, K);
+    case 7: return run<EPI, 64, 128, 64, 3, 2, 2>(ctx, s, A, W, C, Res, M, N, K);
+    default: return run<EPI, 160, 256, 64, 3, 1, 4>(ctx, s, A, W, C, Res, M, N, K);
   }
 }
 
