@@ -3,9 +3,11 @@
 // >90% of a PVF round's time (the batched forward over backbone + drafts, Sec. 4.1).
 //
 // Shape of the kernel
-//   * workgroup tile BM x BN (256 or 128 each), 4 waves in a 2 x 2 grid, each wave
-//     (BM/2) x (BN/2) as v_mfma_f32_32x32x16_bf16 tiles (256 accumulator registers per lane at
-//     256 x 256);
+//   * workgroup tile BM x BN, WM x WN waves, each wave (BM/WM) x (BN/WN) as
+//     v_mfma_f32_32x32x16_bf16 tiles.  The shapes in use: 256 x 256 with 8 waves (2 x 4) for the
+//     wide layers; 192 / 160 / 96 x 256 and 128 x 256, 256 x 128, 128 x 128 with 4 waves where they
+//     put (nearly) one tile on every CU; 64 x 64 and 64 x 128 for launches with few rows, which
+//     stream the weights and want many workgroups with deep rings (pick_config);
 //   * both operands are K-contiguous in memory, so a 16-byte chunk is 8 consecutive k of one
 //     row.  K advances in stages of BK (64 or 32) through a ring of LDS buffers; tiles go from
 //     global memory straight into LDS (global_load_lds_dwordx4, no register staging) ahead of
@@ -318,7 +320,7 @@ pvf_status run(pvf_ctx *ctx, hipStream_t s, const void *A, const void *W, void *
 }
 
 struct TileCfg { int bm, bn, bk, stages; double eff; };
-constexpr int kNumCfg = 9;
+constexpr int kNumCfg = 10;
 constexpr TileCfg kCfg[kNumCfg] = {
     {256, 256, 32, 4, 1.00},   // 8 waves
     {128, 256, 64, 3, 0.85}, {256, 128, 64, 3, 0.85}, {128, 128, 64, 4, 0.80},
@@ -326,7 +328,8 @@ constexpr TileCfg kCfg[kNumCfg] = {
     {192, 256, 32, 4, 0.97},   // fills the chip when M / 256 leaves many CUs idle
     {64, 64, 64, 5, 0.0},      // few rows (window forward of the K/V-cached rounds): the GEMM streams the weights,
     {64, 128, 64, 3, 0.0},     // so many small workgroups with deep rings; chosen by pick_config for M <= 320
-    {160, 256, 64, 3, 0.90}};  // 2560 rows = 16 tile rows: with N = 4096 exactly one tile per CU
+    {160, 256, 64, 3, 0.90},   // 2560 rows = 16 tile rows: with N = 4096 exactly one tile per CU
+    {96, 256, 64, 3, 0.85}};   // the same for 1536 rows
 
 template <int EPI>
 pvf_status run_cfg(pvf_ctx *ctx, hipStream_t s, int cfg, const void *A, const void *W, void *C,
@@ -340,7 +343,8 @@ pvf_status run_cfg(pvf_ctx *ctx, hipStream_t s, int cfg, const void *A, const vo
     case 5: return run<EPI, 192, 256, 32, 4, 2, 2>(ctx, s, A, W, C, Res, M, N, K);
     case 6: if constexpr (EPI != kEpiSwiglu) return run<EPI, 64, 64, 64, 5, 2, 2>(ctx, s, A, W, C, Res, M, N, K);
     case 7: return run<EPI, 64, 128, 64, 3, 2, 2>(ctx, s, A, W, C, Res, M, N, K);
-    default: return run<EPI, 160, 256, 64, 3, 1, 4>(ctx, s, A, W, C, Res, M, N, K);
+    case 8: return run<EPI, 160, 256, 64, 3, 1, 4>(ctx, s, A, W, C, Res, M, N, K);
+    default: return run<EPI, 96, 256, 64, 3, 1, 4>(ctx, s, A, W, C, Res, M, N, K);
   }
 }
 
