@@ -273,6 +273,15 @@ pvf_status pvf_rmsnorm(void *stream, int32_t dtype, const void *x, const void *g
 pvf_status pvf_rope_attention(void *stream, int32_t dtype, void *qkv, void *out, int32_t S,
                               int32_t T, int32_t n_heads, int32_t d_head, float rope_theta);
 
+/* The attention half of a layer as the forward runs it: qkv[S*T, 3*d] = x[S*T, d] * wqkv[3*d, d]^T,
+ * rotary embedding of q and k, out[S*T, d] = attention.  On return qkv holds rotated q | rotated k
+ * | v.  With bf16, d_head = 128 and T % 64 == 0 the rotation and the key-contiguous copy of v that
+ * the attention kernel reads are fused into the projection's epilogue; the results equal
+ * pvf_gemm followed by pvf_rope_attention up to the rounding of one fused multiply-add. */
+pvf_status pvf_qkv_attention(void *stream, int32_t dtype, const void *x, const void *wqkv, void *qkv,
+                             void *out, int32_t S, int32_t T, int32_t n_heads, int32_t d_head,
+                             float rope_theta);
+
 /* Fills dev buffer with n values ~ N(0, std^2) (+ mean) from a counter-based generator;
  * used to materialise random-init weights of benchmark shapes directly in HBM. */
 pvf_status pvf_fill_normal(void *stream, int32_t dtype, void *dst, int64_t n, uint64_t seed,

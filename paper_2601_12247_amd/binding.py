@@ -29,7 +29,7 @@ EXPORTS = ["pvf_create", "pvf_destroy", "pvf_last_error", "pvf_workspace_bytes",
            "pvf_profile_end", "pvf_forward",
            "pvf_epilogue", "pvf_round", "pvf_state_init", "pvf_decode", "pvf_stage1", "pvf_gemm",
            "pvf_gemm_swiglu", "pvf_rmsnorm", "pvf_rope_attention", "pvf_fill_normal", "pvf_entropy",
-           "pvf_plan_vocab_select"]
+           "pvf_plan_vocab_select", "pvf_qkv_attention"]
 
 
 class PvfError(RuntimeError):
@@ -124,6 +124,8 @@ def lib() -> C.CDLL:
                                   C.c_int32, C.c_int32, C.c_float]
         L.pvf_rope_attention.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_int32,
                                          C.c_int32, C.c_int32, C.c_int32, C.c_float]
+        L.pvf_qkv_attention.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                        C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_float]
         L.pvf_fill_normal.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_int64, C.c_uint64,
                                       C.c_float, C.c_float]
         for name in EXPORTS:
@@ -379,10 +381,24 @@ def rmsnorm(x: torch.Tensor, gain: torch.Tensor, eps: float) -> torch.Tensor:
 def rope_attention(qkv: torch.Tensor, S: int, T: int, n_heads: int, d_head: int,
                    rope_theta: float) -> torch.Tensor:
     """qkv [S*T, 3*d] is rotated in place; returns the attention output [S*T, d]."""
+    assert qkv.shape == (S * T, 3 * n_heads * d_head) and qkv.is_contiguous()
     out = torch.empty(S * T, n_heads * d_head, dtype=qkv.dtype, device=qkv.device)
     _check(lib().pvf_rope_attention(_stream(), _dtype_code(qkv.dtype), _ptr(qkv), _ptr(out), S, T,
                                     n_heads, d_head, rope_theta))
     return out
+
+
+def qkv_attention(x: torch.Tensor, wqkv: torch.Tensor, S: int, T: int, n_heads: int, d_head: int,
+                  rope_theta: float):
+    """(qkv [S*T, 3d] with q, k rotated; attention output [S*T, d]) of x [S*T, d]."""
+    d = n_heads * d_head
+    assert x.shape == (S * T, d) and wqkv.shape == (3 * d, d) and x.is_contiguous() and wqkv.is_contiguous()
+    assert wqkv.dtype == x.dtype
+    qkv = torch.empty(S * T, 3 * d, dtype=x.dtype, device=x.device)
+    out = torch.empty(S * T, d, dtype=x.dtype, device=x.device)
+    _check(lib().pvf_qkv_attention(_stream(), _dtype_code(x.dtype), _ptr(x), _ptr(wqkv), _ptr(qkv), _ptr(out),
+                                   S, T, n_heads, d_head, rope_theta))
+    return qkv, out
 
 
 def fill_normal(dst: torch.Tensor, seed: int, mean: float = 0.0, std: float = 0.02) -> None:

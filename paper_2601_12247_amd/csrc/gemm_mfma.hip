@@ -1,5 +1,6 @@
 // bf16 GEMM on the CDNA4 matrix cores:  C[M,N] = A[M,K] * W[N,K]^T, float32 accumulation,
-// with the forward's fused epilogues (plain store, + residual, SwiGLU).  These GEMMs are
+// with the forward's fused epilogues (plain store, + residual, SwiGLU, and for the QKV projection
+// the rotary embedding of q, k plus the key-contiguous copy of v).  These GEMMs are
 // >90% of a PVF round's time (the batched forward over backbone + drafts, Sec. 4.1).
 //
 // Shape of the kernel
@@ -19,7 +20,8 @@
 //     which global chunk a lane fetches, because the LDS slot of a direct load is fixed by the
 //     lane id;
 //   * the W tile is fed as the MFMA "A" operand and the activation tile as "B", so a lane ends
-//     up with 4 consecutive output columns per accumulator group and stores 8 bytes at a time;
+//     up with 4 consecutive output columns per accumulator group; the epilogue turns 32 rows at
+//     a time around through LDS and stores whole 16-byte pieces of 128-byte lines;
 //   * workgroup ids are remapped so that the 32 workgroups resident on one XCD (ids congruent
 //     mod 8) cover a patch of 8 x 4 output tiles and share operand tiles through that XCD's L2.
 #include "common.h"
@@ -67,13 +69,24 @@ __device__ __forceinline__ int w_row(int r, int tile_n, int ff) {
 // workgroups per CU (by LDS) x waves per workgroup / 4 SIMDs
 constexpr int waves_per_simd(int lds_bytes, int waves) { return (lds_bytes <= 80 * 1024 ? 2 : 1) * waves / 4; }
 
+// kEpiQkvRope: the GEMM is the QKV projection of canvases of T tokens (d_head = 128, N = 3 * H * 128).
+// Its epilogue rotates the q and k thirds (rotary embedding, pair (i, i + 64) of each head, angle
+// of canvas position row % T from the cos_sin table [T][64]) before storing them, and writes the
+// v third a second time key-contiguous, vt[canvas][head][d][t], the layout the attention kernel
+// reads its values in.
+struct RopeArgs {
+  const float2 *cos_sin;
+  bf16_t *vt;
+  int32_t T, H;
+};
+
 template <int EPI, int BM, int BN, int BK, int kStages, int WM, int WN>
 __global__ void __launch_bounds__(64 * WM * WN)
 __attribute__((amdgpu_waves_per_eu(waves_per_simd(kStages * (BM + BN) * BK * 2, WM * WN),
                                    waves_per_simd(kStages * (BM + BN) * BK * 2, WM * WN))))
 gemm_bf16_mfma_kernel(const bf16_t *__restrict__ A, const bf16_t *__restrict__ W,
                       bf16_t *__restrict__ C, const bf16_t *__restrict__ Res, int M, int N_out,
-                      int K, int tiles_m, int tiles_n, int group_m) {
+                      int K, int tiles_m, int tiles_n, int group_m, RopeArgs ra) {
   constexpr int kThreads = 64 * WM * WN;
   constexpr int MT = BM / (32 * WM), NT = BN / (32 * WN);  // MFMA tiles per wave in each direction
   constexpr int kATile = BM * BK * 2, kWTile = BN * BK * 2, kStage = kATile + kWTile;
@@ -271,6 +284,71 @@ gemm_bf16_mfma_kernel(const bf16_t *__restrict__ A, const bf16_t *__restrict__ W
                                                                    pack_bf16x2(acc[nt][mt][4 * i + 2], acc[nt][mt][4 * i + 3]));
         }
     }
+    if (EPI == kEpiQkvRope) {
+      static_assert(EPI != kEpiQkvRope || ((WTN == 64 && WN % 2 == 0) || WTN == 128), "a head is one or two wave tiles wide");
+      const int d_model = N_out / 3;
+      const int third = (tile_n * BN) / d_model;                     // 0 = q, 1 = k, 2 = v (uniform per workgroup)
+      const int m_base = m0 + wm * WTM + mt * 32;
+      if (WTN == 64) __syncthreads();                                // the partner wave's half of the head is staged
+      if (third < 2) {
+        const int col_in_head = (out_col0 + rd_col) & 127;
+        const bool upper = col_in_head >= 64;
+        const unsigned char *partner = (WTN == 64) ? lds + (wave ^ 1) * (32 * kStride) + rd_col * 2
+                                                   : my + (rd_col ^ 64) * 2;
+#pragma unroll
+        for (int j = 0; j < 32 / kRowsPerInstr; ++j) {
+          const int r = j * kRowsPerInstr + rd_row;
+          const int m = m_base + r;
+          const uint4 own = *reinterpret_cast<const uint4 *>(my + r * kStride + rd_col * 2);
+          const uint4 oth = *reinterpret_cast<const uint4 *>(partner + r * kStride);
+          if (m < M) {
+            const float2 *cs = ra.cos_sin + (int64_t)(m % ra.T) * 64 + (col_in_head & 63);
+            const uint32_t ow[4] = {own.x, own.y, own.z, own.w}, pw[4] = {oth.x, oth.y, oth.z, oth.w};
+            uint32_t res[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              const float2 c0 = cs[2 * e], c1 = cs[2 * e + 1];
+              const float a0 = __uint_as_float(ow[e] << 16), a1 = __uint_as_float(ow[e] & 0xffff0000u);
+              const float b0 = __uint_as_float(pw[e] << 16), b1 = __uint_as_float(pw[e] & 0xffff0000u);
+              // lower half: x*cos - partner*sin; upper half: x*cos + partner*sin
+              const float r0 = upper ? a0 * c0.x + b0 * c0.y : a0 * c0.x - b0 * c0.y;
+              const float r1 = upper ? a1 * c1.x + b1 * c1.y : a1 * c1.x - b1 * c1.y;
+              res[e] = pack_bf16x2(r0, r1);
+            }
+            *reinterpret_cast<uint4 *>(C + (int64_t)m * N_out + out_col0 + rd_col) = make_uint4(res[0], res[1], res[2], res[3]);
+          }
+        }
+      } else {
+#pragma unroll
+        for (int j = 0; j < 32 / kRowsPerInstr; ++j) {               // v as it is ...
+          const int r = j * kRowsPerInstr + rd_row;
+          const int m = m_base + r;
+          if (m < M) *reinterpret_cast<uint4 *>(C + (int64_t)m * N_out + out_col0 + rd_col) =
+                         *reinterpret_cast<const uint4 *>(my + r * kStride + rd_col * 2);
+        }
+        if (m_base < M) {                                            // ... and key-contiguous: lane = one d column, 32 keys
+          const int seq = m_base / ra.T, t0 = m_base % ra.T;
+          const int vcol0 = out_col0 - 2 * d_model;                  // column inside the v third
+#pragma unroll
+          for (int cc = 0; cc < WTN / 64; ++cc) {
+            const int c = cc * 64 + lane;
+            uint32_t w[16];
+#pragma unroll
+            for (int r2 = 0; r2 < 16; ++r2) {
+              const uint32_t lo = *reinterpret_cast<const uint16_t *>(my + (2 * r2) * kStride + c * 2);
+              const uint32_t hi = *reinterpret_cast<const uint16_t *>(my + (2 * r2 + 1) * kStride + c * 2);
+              w[r2] = lo | (hi << 16);
+            }
+            const int head = (vcol0 + c) >> 7, dcol = (vcol0 + c) & 127;
+            uint4 *dst = reinterpret_cast<uint4 *>(ra.vt + (((int64_t)seq * ra.H + head) * 128 + dcol) * ra.T + t0);
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4) dst[q4] = make_uint4(w[4 * q4], w[4 * q4 + 1], w[4 * q4 + 2], w[4 * q4 + 3]);
+          }
+        }
+      }
+      if (WTN == 64) __syncthreads();                                // before the next 32 rows overwrite the staging area
+      continue;
+    }
 #pragma unroll
     for (int j = 0; j < 32 / kRowsPerInstr; ++j) {
       const int r = j * kRowsPerInstr + rd_row;
@@ -296,7 +374,7 @@ gemm_bf16_mfma_kernel(const bf16_t *__restrict__ A, const bf16_t *__restrict__ W
 
 template <int EPI, int BM, int BN, int BK, int ST, int WM, int WN>
 pvf_status run(pvf_ctx *ctx, hipStream_t s, const void *A, const void *W, void *C, const void *Res,
-               int M, int N_out, int K) {
+               int M, int N_out, int K, const RopeArgs &ra) {
   constexpr int kLdsBytes = ST * (BM + BN) * BK * 2;
   static_assert(kLdsBytes <= 160 * 1024, "LDS ring exceeds the 160 KB of a CU");
   static bool configured = false;
@@ -314,7 +392,7 @@ pvf_status run(pvf_ctx *ctx, hipStream_t s, const void *A, const void *W, void *
   const int n_bands = (tiles_m + 7) / 8;
   const int group_m = (tiles_m + n_bands - 1) / n_bands;
   gemm_bf16_mfma_kernel<EPI, BM, BN, BK, ST, WM, WN><<<grid, 64 * WM * WN, kLdsBytes, s>>>(
-      (const bf16_t *)A, (const bf16_t *)W, (bf16_t *)C, (const bf16_t *)Res, M, N_out, K, tiles_m, tiles_n, group_m);
+      (const bf16_t *)A, (const bf16_t *)W, (bf16_t *)C, (const bf16_t *)Res, M, N_out, K, tiles_m, tiles_n, group_m, ra);
   PVF_LAUNCH_CHECK(ctx, "gemm_mfma");
   return PVF_OK;
 }
@@ -333,18 +411,18 @@ constexpr TileCfg kCfg[kNumCfg] = {
 
 template <int EPI>
 pvf_status run_cfg(pvf_ctx *ctx, hipStream_t s, int cfg, const void *A, const void *W, void *C,
-                   const void *Res, int M, int N, int K) {
+                   const void *Res, int M, int N, int K, const RopeArgs &ra = RopeArgs{}) {
   switch (cfg) {
-    case 0: return run<EPI, 256, 256, 32, 4, 2, 4>(ctx, s, A, W, C, Res, M, N, K);
-    case 1: return run<EPI, 128, 256, 64, 3, 2, 2>(ctx, s, A, W, C, Res, M, N, K);
-    case 2: return run<EPI, 256, 128, 64, 3, 2, 2>(ctx, s, A, W, C, Res, M, N, K);
-    case 3: return run<EPI, 128, 128, 64, 4, 2, 2>(ctx, s, A, W, C, Res, M, N, K);
-    case 4: return run<EPI, 256, 256, 32, 4, 2, 2>(ctx, s, A, W, C, Res, M, N, K);
-    case 5: return run<EPI, 192, 256, 32, 4, 2, 2>(ctx, s, A, W, C, Res, M, N, K);
-    case 6: if constexpr (EPI != kEpiSwiglu) return run<EPI, 64, 64, 64, 5, 2, 2>(ctx, s, A, W, C, Res, M, N, K);
-    case 7: return run<EPI, 64, 128, 64, 3, 2, 2>(ctx, s, A, W, C, Res, M, N, K);
-    case 8: return run<EPI, 160, 256, 64, 3, 1, 4>(ctx, s, A, W, C, Res, M, N, K);
-    default: return run<EPI, 96, 256, 64, 3, 1, 4>(ctx, s, A, W, C, Res, M, N, K);
+    case 0: return run<EPI, 256, 256, 32, 4, 2, 4>(ctx, s, A, W, C, Res, M, N, K, ra);
+    case 1: return run<EPI, 128, 256, 64, 3, 2, 2>(ctx, s, A, W, C, Res, M, N, K, ra);
+    case 2: return run<EPI, 256, 128, 64, 3, 2, 2>(ctx, s, A, W, C, Res, M, N, K, ra);
+    case 3: return run<EPI, 128, 128, 64, 4, 2, 2>(ctx, s, A, W, C, Res, M, N, K, ra);
+    case 4: return run<EPI, 256, 256, 32, 4, 2, 2>(ctx, s, A, W, C, Res, M, N, K, ra);
+    case 5: return run<EPI, 192, 256, 32, 4, 2, 2>(ctx, s, A, W, C, Res, M, N, K, ra);
+    case 6: if constexpr (EPI != kEpiSwiglu && EPI != kEpiQkvRope) return run<EPI, 64, 64, 64, 5, 2, 2>(ctx, s, A, W, C, Res, M, N, K, ra);
+    case 7: return run<EPI, 64, 128, 64, 3, 2, 2>(ctx, s, A, W, C, Res, M, N, K, ra);
+    case 8: return run<EPI, 160, 256, 64, 3, 1, 4>(ctx, s, A, W, C, Res, M, N, K, ra);
+    default: return run<EPI, 96, 256, 64, 3, 1, 4>(ctx, s, A, W, C, Res, M, N, K, ra);
   }
 }
 
@@ -360,7 +438,7 @@ int pick_config(GemmEpilogue epi, int M, int N, int K) {
   // The output head (N = vocabulary) has enough tiles to fill the chip at any M > 64 and goes by the
   // cost model below.
   if (forced < 0 && M <= 384 && K % 64 == 0 && (M <= 64 || N <= 32768)) {
-    if (epi != kEpiSwiglu && M <= 128 && N % 64 == 0) return 6;
+    if (epi != kEpiSwiglu && epi != kEpiQkvRope && M <= 128 && N % 64 == 0) return 6;
     if (N % (epi == kEpiSwiglu ? 64 : 128) == 0) return 7;
   }
   int best = -1;
@@ -379,6 +457,28 @@ int pick_config(GemmEpilogue epi, int M, int N, int K) {
 
 }  // namespace
 
+bool gemm_mfma_supported(int dtype, GemmEpilogue epi, int M, int N, int K);
+
+// QKV projection with the rotary embedding and the key-contiguous copy of v fused into the
+// epilogue (see RopeArgs).  qkv [M, 3*H*128], vt [M/T, H, 128, T], cos_sin [T, 64].
+bool gemm_mfma_qkv_rope_supported(int dtype, int M, int N, int K, int T, int H) {
+  if (!gemm_mfma_supported(dtype, kEpiStore, M, N, K)) return false;
+  if (N != 3 * H * 128 || H % 2 != 0 || T % 32 != 0 || M % T != 0) return false;
+  const int cfg = pick_config(kEpiQkvRope, M, N, K);
+  return cfg >= 0 && cfg != 6;
+}
+
+pvf_status launch_gemm_mfma_qkv_rope(pvf_ctx *ctx, hipStream_t s, const void *A, const void *W, void *qkv,
+                                     void *vt, const float2 *cos_sin, int M, int N, int K, int T, int H) {
+  const uintptr_t al = (uintptr_t)A | (uintptr_t)W | (uintptr_t)qkv | (uintptr_t)vt;
+  PVF_REQUIRE(ctx, (al & 15u) == 0, PVF_EINVAL, "gemm_mfma: operands must be 16-byte aligned");
+  const int cfg = pick_config(kEpiQkvRope, M, N, K);
+  PVF_REQUIRE(ctx, cfg >= 0 && cfg != 6, PVF_ESHAPE, "gemm_mfma: no tile shape with a rotary epilogue for N=%d", N);
+  RopeArgs ra;
+  ra.cos_sin = cos_sin; ra.vt = (bf16_t *)vt; ra.T = T; ra.H = H;
+  return run_cfg<kEpiQkvRope>(ctx, s, cfg, A, W, qkv, nullptr, M, N, K, ra);
+}
+
 bool gemm_mfma_supported(int dtype, GemmEpilogue epi, int M, int N, int K) {
   if (dtype != PVF_BF16 || M < 1 || K < 64 || K % 64 != 0) return false;
   const int64_t w_rows = (epi == kEpiSwiglu) ? 2 * (int64_t)N : N;
@@ -396,6 +496,7 @@ pvf_status launch_gemm_mfma(pvf_ctx *ctx, hipStream_t s, GemmEpilogue epi, const
     case kEpiStore: return run_cfg<kEpiStore>(ctx, s, cfg, A, W, C, residual, M, N, K);
     case kEpiResidual: return run_cfg<kEpiResidual>(ctx, s, cfg, A, W, C, residual, M, N, K);
     case kEpiSwiglu: return run_cfg<kEpiSwiglu>(ctx, s, cfg, A, W, C, residual, M, N, K);
+    case kEpiQkvRope: break;                     // has its own entry (launch_gemm_mfma_qkv_rope)
   }
   return PVF_EINVAL;
 }

@@ -81,6 +81,9 @@ pvf_status launch_attention_simple(pvf_ctx *, hipStream_t, int, const void *, vo
 bool gemm_mfma_supported(int dtype, GemmEpilogue epi, int M, int N, int K);
 pvf_status launch_gemm_mfma(pvf_ctx *, hipStream_t, GemmEpilogue, const void *, const void *, void *,
                             const void *, int, int, int);
+bool gemm_mfma_qkv_rope_supported(int dtype, int M, int N, int K, int T, int H);
+pvf_status launch_gemm_mfma_qkv_rope(pvf_ctx *, hipStream_t, const void *, const void *, void *, void *, const float2 *,
+                                     int, int, int, int, int);
 bool attention_mfma_supported(int dtype, int T, int d_head);
 pvf_status launch_attention_mfma(pvf_ctx *, hipStream_t, const void *, const void *, void *, int, int, int);
 pvf_status launch_rope_vt(pvf_ctx *, hipStream_t, void *, void *, int, int, int, const float2 *);
@@ -279,11 +282,21 @@ static pvf_status forward_impl(pvf_ctx *c, hipStream_t s, const int32_t *tokens,
                                      (double)(Mm) * (Nn) * ((epi) == kEpiResidual ? 2 : 1)));             \
     RUN(launch_gemm(c, s, dt, epi, A, W, C, res, Mm, Nn, Kk));                                    \
   } while (0)
+  const bool fused_rope = use_attention_mfma(dt, T, dh) && gemm_mfma_qkv_rope_supported(dt, M, 3 * d, d, T, H);
   RUN(launch_embed(c, s, dt, c->w.embed, tokens, seq_slot, S, T, d, m.vocab, c->h));
   for (int l = 0; l < m.n_layers; ++l) {
     RUN(launch_rmsnorm(c, s, dt, c->h, c->attn_norm[l], c->xn, M, d, m.rms_eps));
-    RUN_GEMM(kEpiStore, c->xn, c->wqkv[l], c->qkv, nullptr, M, 3 * d, d);
-    {
+    if (fused_rope) {
+      // the QKV projection rotates q, k and writes the key-contiguous v in its epilogue
+      {
+        ProfScope ps(c, s, PVF_PROF_GEMM, 2.0 * M * (double)(3 * d) * d,
+                     (double)c->esize * ((double)M * d + 3.0 * d * d + (double)M * 3 * d));
+        RUN(launch_gemm_mfma_qkv_rope(c, s, c->xn, c->wqkv[l], c->qkv, c->vt, c->cos_sin, M, 3 * d, d, T, H));
+      }
+      ProfScope ps(c, s, PVF_PROF_ATTENTION, 4.0 * S * (double)T * T * d, 0.0);
+      RUN(launch_attention_mfma(c, s, c->qkv, c->vt, c->att, S, T, H));
+    } else {
+      RUN_GEMM(kEpiStore, c->xn, c->wqkv[l], c->qkv, nullptr, M, 3 * d, d);
       ProfScope ps(c, s, PVF_PROF_ATTENTION, 4.0 * S * (double)T * T * d, 0.0);
       RUN(launch_rope_attention(c, s, dt, c->qkv, c->vt, c->att, S, T, H, dh, c->cos_sin));
     }
@@ -706,6 +719,47 @@ extern "C" pvf_status pvf_rope_attention(void *stream, int32_t dtype, void *qkv,
     if (e != hipSuccess) { set_error(nullptr, "scratch allocation: %s", hipGetErrorString(e)); st = PVF_EHIP; }
   }
   if (st == PVF_OK) st = launch_rope_attention(nullptr, s, dtype, qkv, vt, out, S, T, n_heads, d_head, dev);
+  (void)hipStreamSynchronize(s);
+  (void)hipFree(dev);
+  if (vt) (void)hipFree(vt);
+  return st;
+}
+
+extern "C" pvf_status pvf_qkv_attention(void *stream, int32_t dtype, const void *x, const void *wqkv, void *qkv,
+                                        void *out, int32_t S, int32_t T, int32_t n_heads, int32_t d_head,
+                                        float rope_theta) {
+  if (check_dtype(dtype) != PVF_OK) return PVF_EINVAL;
+  PVF_REQUIRE(nullptr, x && wqkv && qkv && out && S >= 0 && T > 0 && n_heads > 0 && d_head > 0 && d_head % 2 == 0 &&
+                  rope_theta > 0.f, PVF_EINVAL, "pvf_qkv_attention: bad argument");
+  if (S == 0) return PVF_OK;
+  hipStream_t s = (hipStream_t)stream;
+  const int half = d_head / 2, d = n_heads * d_head, M = S * T;
+  std::vector<float2> tab((size_t)T * half);
+  for (int i = 0; i < half; ++i) {
+    const double inv = std::pow((double)rope_theta, -2.0 * i / d_head);
+    for (int t = 0; t < T; ++t)
+      tab[(size_t)t * half + i] = make_float2((float)std::cos(t * inv), (float)std::sin(t * inv));
+  }
+  float2 *dev = nullptr;
+  void *vt = nullptr;
+  PVF_HIP_CHECK(nullptr, hipMalloc((void **)&dev, tab.size() * sizeof(float2)));
+  hipError_t e = hipMemcpy(dev, tab.data(), tab.size() * sizeof(float2), hipMemcpyHostToDevice);
+  pvf_status st = PVF_OK;
+  if (e != hipSuccess) { set_error(nullptr, "rotary table upload: %s", hipGetErrorString(e)); st = PVF_EHIP; }
+  const bool mfma_att = use_attention_mfma(dtype, T, d_head);
+  if (st == PVF_OK && mfma_att) {
+    e = hipMalloc(&vt, (size_t)M * d * 2);
+    if (e != hipSuccess) { set_error(nullptr, "scratch allocation: %s", hipGetErrorString(e)); st = PVF_EHIP; }
+  }
+  if (st == PVF_OK) {
+    if (mfma_att && gemm_mfma_qkv_rope_supported(dtype, M, 3 * d, d, T, n_heads)) {
+      st = launch_gemm_mfma_qkv_rope(nullptr, s, x, wqkv, qkv, vt, dev, M, 3 * d, d, T, n_heads);
+      if (st == PVF_OK) st = launch_attention_mfma(nullptr, s, qkv, vt, out, S, T, n_heads);
+    } else {
+      st = launch_gemm(nullptr, s, dtype, kEpiStore, x, wqkv, qkv, nullptr, M, 3 * d, d);
+      if (st == PVF_OK) st = launch_rope_attention(nullptr, s, dtype, qkv, vt, out, S, T, n_heads, d_head, dev);
+    }
+  }
   (void)hipStreamSynchronize(s);
   (void)hipFree(dev);
   if (vt) (void)hipFree(vt);

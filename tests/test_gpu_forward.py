@@ -90,6 +90,31 @@ def test_rope_attention(S_, T, H, dh, theta, dtype):
     np.testing.assert_allclose(got, want, atol=3e-5 if dtype == torch.float32 else 2e-2, rtol=0)
 
 
+@pytest.mark.parametrize("S_,T,H", [(5, 512, 32), (9, 1280, 32), (3, 512, 32), (1, 64, 2), (3, 96, 2), (2, 320, 4),
+                                    (1, 1280, 6), (7, 160, 8)])
+def test_qkv_attention_fused_epilogue_equals_separate_passes(S_, T, H):
+    """The projection whose epilogue rotates q, k and writes the key-contiguous v, followed by the
+    attention kernel, against pvf_gemm + pvf_rope_attention (rotation as a pass of its own)."""
+    dh, d = 128, H * 128
+    K = d                                                  # the projection maps d_model to 3 * d_model
+    g = torch.Generator(device="cuda").manual_seed(S_ * T + H)
+    x = torch.randn(S_ * T, K, device="cuda", generator=g).to(torch.bfloat16)
+    w = (torch.randn(3 * d, K, device="cuda", generator=g) * (1.6 / K ** 0.5)).to(torch.bfloat16)   # scores of std ~2.5
+    qkv, out = B.qkv_attention(x, w, S_, T, H, dh, 5e5)
+    ref_qkv = B.gemm(x, w)
+    v_plain = ref_qkv[:, 2 * d:].clone()
+    ref_out = B.rope_attention(ref_qkv, S_, T, H, dh, 5e5)  # rotates ref_qkv in place
+    torch.cuda.synchronize()
+    assert torch.equal(qkv[:, 2 * d:], v_plain)             # v is stored unchanged
+    a, b = qkv[:, : 2 * d].float(), ref_qkv[:, : 2 * d].float()
+    # the same fp32 formula on both sides, up to the contraction of one multiply-add before the bf16 rounding
+    assert (a - b).abs().max().item() <= 2 ** -7 * b.abs().max().item()
+    assert (a != b).float().mean().item() < 0.02
+    scale = ref_out.float().abs().max().item()
+    assert scale > 0.3                                      # sharp enough that misplaced keys would show
+    assert (out.float() - ref_out.float()).abs().max().item() <= 2e-2 * scale
+
+
 def test_forward_tiny_fp32_logits_within_1e4():
     shape = S.TINY
     w = S.make_weights(shape, seed=0)
