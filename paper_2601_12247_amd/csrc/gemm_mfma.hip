@@ -96,6 +96,12 @@ gemm_bf16_mfma_kernel(const bf16_t *__restrict__ A, const bf16_t *__restrict__ W
   constexpr int LA = BM / RPI, LW = BN / RPI;        // direct loads per thread per stage
   constexpr int KS = BK / 16;                        // MFMA k-steps per stage
   constexpr int kRowBytes = BK * 2;
+  // With a ring of only two stages the refill of a slot is issued as soon as the slot is free (right
+  // after the barrier in the last k-step of the stage that was read from it), all of it in that one
+  // k-step: the loads of stage kt + 2 then have a whole stage to land.  Deeper rings spread the refill
+  // of the slot freed one stage ago over the first k-steps of a stage.
+  constexpr bool kLate = kStages == 2;
+  constexpr int kAhead = kLate ? kStages : kStages - 1;     // stages in flight after the prologue
   static_assert(BM % RPI == 0 && BN % RPI == 0 && KS >= 2, "tile shape");
   static_assert(EPI != kEpiSwiglu || NT % 2 == 0, "SwiGLU pairs gate/up sub-tiles inside a wave");
   extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
@@ -160,7 +166,7 @@ gemm_bf16_mfma_kernel(const bf16_t *__restrict__ A, const bf16_t *__restrict__ W
 
   const int nk = K / BK;
 #pragma unroll
-  for (int s = 0; s < kStages - 1; ++s)
+  for (int s = 0; s < kAhead; ++s)
     if (s < nk) {
 #pragma unroll
       for (int i = 0; i < kLoadsPerStage; ++i) issue_one(s, i);
@@ -169,7 +175,7 @@ gemm_bf16_mfma_kernel(const bf16_t *__restrict__ A, const bf16_t *__restrict__ W
   // Waits until at most n whole stages of this wave's direct loads are still in flight.
   auto wait_stages = [&](int n) {
     if (kStages >= 4 && n >= 2) wait_vmcnt<2 * kLoadsPerStage>();
-    else if (kStages >= 3 && n >= 1) wait_vmcnt<kLoadsPerStage>();
+    else if ((kStages >= 3 || kLate) && n >= 1) wait_vmcnt<kLoadsPerStage>();
     else wait_vmcnt<0>();
   };
   // Fragment j of a k-step in the order the MFMAs below first need them: W 0, A 0..MT-1, W 1..
@@ -192,7 +198,7 @@ gemm_bf16_mfma_kernel(const bf16_t *__restrict__ A, const bf16_t *__restrict__ W
   constexpr int kMfmaPerStep = MT * NT, kDsPerStep = MT + NT;
   constexpr int kVmPerStep = (kLoadsPerStage + KS - 2) / (KS - 1);
   constexpr int kDsPerMfma = (kDsPerStep + kMfmaPerStep - 1) / kMfmaPerStep;   // 1 except for the small-M shapes
-  wait_stages(min(kStages - 2, nk - 1));
+  wait_stages(min(kAhead - 1, nk - 1));
   __builtin_amdgcn_s_barrier();
 #pragma unroll
   for (int j = 0; j < kDsPerStep; ++j) read_one(lds, 0, 0, j);
@@ -223,17 +229,21 @@ gemm_bf16_mfma_kernel(const bf16_t *__restrict__ A, const bf16_t *__restrict__ W
           for (int q = 0; q < kDsPerMfma; ++q)
             if (i * kDsPerMfma + q < kDsPerStep) read_one(last ? next : stage, last ? 0 : kk + 1, nxt, i * kDsPerMfma + q);
         }
-        if (kSteady && !last) {
+        if (!kLate && kSteady && !last) {
 #pragma unroll
           for (int q = 0; q < kVmPerStep; ++q)
             if ((q * kMfmaPerStep) / kVmPerStep == i && kk * kVmPerStep + q < kLoadsPerStage)
               issue_one(kt + kStages - 1, kk * kVmPerStep + q);
         }
+        if (kLate && kSteady && last) {                      // slot kt % kStages was freed by the barrier above
+          static_assert(!kLate || kLoadsPerStage <= kMfmaPerStep, "one refill load per MFMA of the last k-step");
+          if (i < kLoadsPerStage) issue_one(kt + kStages, i);
+        }
         __builtin_amdgcn_sched_barrier(0);
       }
     }
   };
-  const int n_loading = nk - (kStages - 1);                  // stages that still have a stage to prefetch
+  const int n_loading = nk - kAhead;                         // stages that still have a stage to prefetch
   int kt = 0;
   for (; kt < n_loading; ++kt) run_stage(kt, std::true_type{});
   for (; kt < nk; ++kt) run_stage(kt, std::false_type{});
@@ -252,10 +262,24 @@ gemm_bf16_mfma_kernel(const bf16_t *__restrict__ A, const bf16_t *__restrict__ W
   constexpr int LPR = OC / 8;                                        // lanes per output row (8 columns each)
   constexpr int kRowsPerInstr = 64 / LPR;
   static_assert(WM * WN * 32 * kStride <= kStages * kStage, "staging area exceeds the LDS ring");
-  __syncthreads();                                                   // every wave is done with the ring
-  unsigned char *my = lds + wave * (32 * kStride);
   const int out_col0 = (EPI == kEpiSwiglu ? tile_n * (BN / 2) : tile_n * BN) + wn * OC;
   const int rd_row = lane / LPR, rd_col = (lane % LPR) * 8;
+  // The residual rows of the whole wave tile are requested at once, before the staging starts:
+  // fetched 32 rows at a time where they are added, each piece cost a full memory latency.
+  constexpr int kRowIters = 32 / kRowsPerInstr;
+  uint4 rs[EPI == kEpiResidual ? MT : 1][kRowIters];
+  if (EPI == kEpiResidual) {
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+      for (int j = 0; j < kRowIters; ++j) {
+        const int m = m0 + wm * WTM + mt * 32 + j * kRowsPerInstr + rd_row;
+        rs[mt][j] = make_uint4(0, 0, 0, 0);
+        if (m < M) rs[mt][j] = *reinterpret_cast<const uint4 *>(Res + (int64_t)m * N_out + out_col0 + rd_col);
+      }
+  }
+  __syncthreads();                                                   // every wave is done with the ring
+  unsigned char *my = lds + wave * (32 * kStride);
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt) {
     unsigned char *wrow = my + fr * kStride;
@@ -358,12 +382,11 @@ gemm_bf16_mfma_kernel(const bf16_t *__restrict__ A, const bf16_t *__restrict__ W
       if (EPI == kEpiResidual) {
         const float4 x0 = *reinterpret_cast<const float4 *>(my + r * kStride + rd_col * 4);
         const float4 x1 = *reinterpret_cast<const float4 *>(my + r * kStride + rd_col * 4 + 16);
-        uint4 rs = make_uint4(0, 0, 0, 0);
-        if (m < M) rs = *reinterpret_cast<const uint4 *>(Res + o);
-        out.x = pack_bf16x2(x0.x + __uint_as_float(rs.x << 16), x0.y + __uint_as_float(rs.x & 0xffff0000u));
-        out.y = pack_bf16x2(x0.z + __uint_as_float(rs.y << 16), x0.w + __uint_as_float(rs.y & 0xffff0000u));
-        out.z = pack_bf16x2(x1.x + __uint_as_float(rs.z << 16), x1.y + __uint_as_float(rs.z & 0xffff0000u));
-        out.w = pack_bf16x2(x1.z + __uint_as_float(rs.w << 16), x1.w + __uint_as_float(rs.w & 0xffff0000u));
+        const uint4 r4 = rs[EPI == kEpiResidual ? mt : 0][j];
+        out.x = pack_bf16x2(x0.x + __uint_as_float(r4.x << 16), x0.y + __uint_as_float(r4.x & 0xffff0000u));
+        out.y = pack_bf16x2(x0.z + __uint_as_float(r4.y << 16), x0.w + __uint_as_float(r4.y & 0xffff0000u));
+        out.z = pack_bf16x2(x1.x + __uint_as_float(r4.z << 16), x1.y + __uint_as_float(r4.z & 0xffff0000u));
+        out.w = pack_bf16x2(x1.z + __uint_as_float(r4.w << 16), x1.w + __uint_as_float(r4.w & 0xffff0000u));
       } else {
         out = *reinterpret_cast<const uint4 *>(my + r * kStride + rd_col * 2);
       }
@@ -398,7 +421,7 @@ pvf_status run(pvf_ctx *ctx, hipStream_t s, const void *A, const void *W, void *
 }
 
 struct TileCfg { int bm, bn, bk, stages; double eff; };
-constexpr int kNumCfg = 10;
+constexpr int kNumCfg = 12;
 constexpr TileCfg kCfg[kNumCfg] = {
     {256, 256, 32, 4, 1.00},   // 8 waves
     {128, 256, 64, 3, 0.85}, {256, 128, 64, 3, 0.85}, {128, 128, 64, 4, 0.80},
@@ -407,7 +430,9 @@ constexpr TileCfg kCfg[kNumCfg] = {
     {64, 64, 64, 5, 0.0},      // few rows (window forward of the K/V-cached rounds): the GEMM streams the weights,
     {64, 128, 64, 3, 0.0},     // so many small workgroups with deep rings; chosen by pick_config for M <= 320
     {160, 256, 64, 3, 0.90},   // 2560 rows = 16 tile rows: with N = 4096 exactly one tile per CU
-    {96, 256, 64, 3, 0.85}};   // the same for 1536 rows
+    {96, 256, 64, 3, 0.85},    // the same for 1536 rows
+    {256, 256, 64, 2, 1.07},   // shape 0 with 128-byte rows in a ring of two stages: half as many L2 requests
+    {256, 256, 64, 2, 0.0}};   // the same with 4 waves
 
 template <int EPI>
 pvf_status run_cfg(pvf_ctx *ctx, hipStream_t s, int cfg, const void *A, const void *W, void *C,
@@ -422,7 +447,9 @@ pvf_status run_cfg(pvf_ctx *ctx, hipStream_t s, int cfg, const void *A, const vo
     case 6: if constexpr (EPI != kEpiSwiglu && EPI != kEpiQkvRope) return run<EPI, 64, 64, 64, 5, 2, 2>(ctx, s, A, W, C, Res, M, N, K, ra);
     case 7: return run<EPI, 64, 128, 64, 3, 2, 2>(ctx, s, A, W, C, Res, M, N, K, ra);
     case 8: return run<EPI, 160, 256, 64, 3, 1, 4>(ctx, s, A, W, C, Res, M, N, K, ra);
-    default: return run<EPI, 96, 256, 64, 3, 1, 4>(ctx, s, A, W, C, Res, M, N, K, ra);
+    case 9: return run<EPI, 96, 256, 64, 3, 1, 4>(ctx, s, A, W, C, Res, M, N, K, ra);
+    case 10: return run<EPI, 256, 256, 64, 2, 2, 4>(ctx, s, A, W, C, Res, M, N, K, ra);
+    default: return run<EPI, 256, 256, 64, 2, 2, 2>(ctx, s, A, W, C, Res, M, N, K, ra);
   }
 }
 
