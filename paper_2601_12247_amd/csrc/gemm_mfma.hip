@@ -5,18 +5,21 @@
 //
 // Shape of the kernel
 //   * workgroup tile BM x BN, WM x WN waves, each wave (BM/WM) x (BN/WN) as
-//     v_mfma_f32_32x32x16_bf16 tiles.  The shapes in use: 256 x 256 with 8 waves (2 x 4) for the
+//     v_mfma_f32_16x16x32_bf16 tiles (in a loop that also feeds LDS and direct loads this shape
+//     sustains ~14% more than 32x32x16 at two waves per SIMD, although a loop of nothing but
+//     MFMAs runs both at the same rate).  The shapes in use: 256 x 256 with 8 waves (2 x 4) for the
 //     wide layers; 192 / 160 / 96 x 256 and 128 x 256, 256 x 128, 128 x 128 with 4 waves where they
 //     put (nearly) one tile on every CU; 64 x 64 and 64 x 128 for launches with few rows, which
 //     stream the weights and want many workgroups with deep rings (pick_config);
 //   * both operands are K-contiguous in memory, so a 16-byte chunk is 8 consecutive k of one
-//     row.  K advances in stages of BK (64 or 32) through a ring of LDS buffers; tiles go from
+//     row.  K advances in stages of BK = 64 (whole 128-byte lines per row: half the L2 requests
+//     of 64-byte pieces) through a ring of LDS buffers; tiles go from
 //     global memory straight into LDS (global_load_lds_dwordx4, no register staging) ahead of
 //     the MFMAs; one raw s_barrier per stage, preceded by an explicit s_waitcnt vmcnt(n) that
 //     lets the loads of later stages stay in flight;
-//   * an LDS row is 2*BK bytes (8 or 4 chunks); the chunk position is XOR-swizzled with
-//     (row >> 1) & 7 resp. (row >> 2) & 3 so that the ds_read_b128 of an MFMA operand
-//     (consecutive rows, one chunk) touches every bank once.  The swizzle is applied by choosing
+//   * an LDS row is 128 bytes (8 chunks); the chunk position is XOR-swizzled with
+//     (row >> 1) & 7 so that the ds_read_b128 of an MFMA operand (16 consecutive rows, 4 chunk
+//     positions) touches every bank once per 16 lanes.  The swizzle is applied by choosing
 //     which global chunk a lane fetches, because the LDS slot of a direct load is fixed by the
 //     lane id;
 //   * the W tile is fed as the MFMA "A" operand and the activation tile as "B", so a lane ends
@@ -33,7 +36,7 @@ namespace pvf {
 namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
 
 
 typedef __attribute__((address_space(1))) const void gptr_t;
@@ -54,9 +57,9 @@ template <int N> __device__ __forceinline__ void wait_vmcnt() {
 
 // Row of W that feeds row r (0..BN-1) of the workgroup's W tile.
 //  plain:   consecutive rows tile_n*BN + r.
-//  SwiGLU:  the tile covers BN/2 output columns; inside each wave's BN/WN tile rows the 32-row
-//           MFMA sub-tiles alternate gate / up for the same 32 columns, so silu(g)*u pairs
-//           accumulators of one lane.
+//  SwiGLU:  the tile covers BN/2 output columns; inside each wave's BN/WN tile rows groups of 32
+//           rows alternate gate / up for the same 32 columns, so silu(g)*u pairs accumulators
+//           of one lane (16-row MFMA sub-tiles 4P, 4P+1 with 4P+2, 4P+3).
 template <int EPI, int BN, int WN>
 __device__ __forceinline__ int w_row(int r, int tile_n, int ff) {
   if (EPI != kEpiSwiglu) return tile_n * BN + r;
@@ -88,13 +91,14 @@ gemm_bf16_mfma_kernel(const bf16_t *__restrict__ A, const bf16_t *__restrict__ W
                       bf16_t *__restrict__ C, const bf16_t *__restrict__ Res, int M, int N_out,
                       int K, int tiles_m, int tiles_n, int group_m, RopeArgs ra) {
   constexpr int kThreads = 64 * WM * WN;
-  constexpr int MT = BM / (32 * WM), NT = BN / (32 * WN);  // MFMA tiles per wave in each direction
+  constexpr int MT = BM / (32 * WM);                       // 32-row passes of the epilogue
+  constexpr int MT16 = BM / (16 * WM), NT16 = BN / (16 * WN);   // 16x16 MFMA tiles per wave in each direction
   constexpr int kATile = BM * BK * 2, kWTile = BN * BK * 2, kStage = kATile + kWTile;
   constexpr int CPR = BK / 8;                        // 16-byte chunks per LDS row
   constexpr int RPI = kThreads / CPR;                // tile rows covered by one load instruction of the block
   constexpr int kInstrBytes = kThreads * 16;         // LDS bytes filled by one load instruction of the block
   constexpr int LA = BM / RPI, LW = BN / RPI;        // direct loads per thread per stage
-  constexpr int KS = BK / 16;                        // MFMA k-steps per stage
+  constexpr int KS = BK / 32;                        // MFMA k-steps per stage
   constexpr int kRowBytes = BK * 2;
   // With a ring of only two stages the refill of a slot is issued as soon as the slot is free (right
   // after the barrier in the last k-step of the stage that was read from it), all of it in that one
@@ -102,8 +106,8 @@ gemm_bf16_mfma_kernel(const bf16_t *__restrict__ A, const bf16_t *__restrict__ W
   // of the slot freed one stage ago over the first k-steps of a stage.
   constexpr bool kLate = kStages == 2;
   constexpr int kAhead = kLate ? kStages : kStages - 1;     // stages in flight after the prologue
-  static_assert(BM % RPI == 0 && BN % RPI == 0 && KS >= 2, "tile shape");
-  static_assert(EPI != kEpiSwiglu || NT % 2 == 0, "SwiGLU pairs gate/up sub-tiles inside a wave");
+  static_assert(BM % RPI == 0 && BN % RPI == 0 && BK == 64 && BM % (32 * WM) == 0 && BN % (32 * WN) == 0, "tile shape");
+  static_assert(EPI != kEpiSwiglu || NT16 % 4 == 0, "SwiGLU pairs 32-column gate/up groups inside a wave");
   extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform: LDS targets become scalar arithmetic
@@ -147,22 +151,22 @@ gemm_bf16_mfma_kernel(const bf16_t *__restrict__ A, const bf16_t *__restrict__ W
       __builtin_amdgcn_global_load_lds((gptr_t *)(Wb + koff + w_off[i - LA]), (lptr_t *)(dst + kATile + (i - LA) * kInstrBytes), 16, 0, 0);
   };
 
-  // ---- LDS -> MFMA operands: lane reads row (base + lane%32), chunk (2*kk + lane/32) ----
-  const int fr = lane & 31, fh = lane >> 5;
-  const int swz = CPR == 8 ? (fr >> 1) & 7 : (fr >> 2) & 3;
+  // ---- LDS -> MFMA operands: lane reads row (base + lane%16), chunk (4*kk + lane/16) ----
+  const int fr = lane & 15, fq = lane >> 4;
+  const int swz = (fr >> 1) & 7;
   int frag_off[KS];
 #pragma unroll
-  for (int kk = 0; kk < KS; ++kk) frag_off[kk] = fr * kRowBytes + (((kk * 2 + fh) ^ swz) << 4);
+  for (int kk = 0; kk < KS; ++kk) frag_off[kk] = fr * kRowBytes + (((kk * 4 + fq) ^ swz) << 4);
   const int a_base = wm * (BM / WM) * kRowBytes;             // byte offset of the wave's rows in the A tile
   const int w_base = kATile + wn * (BN / WN) * kRowBytes;
 
-  floatx16 acc[NT][MT];                                      // [n sub-tile][m sub-tile]
+  floatx4 acc[NT16][MT16];                                   // [n sub-tile][m sub-tile]
 #pragma unroll
-  for (int nt = 0; nt < NT; ++nt)
+  for (int nt = 0; nt < NT16; ++nt)
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt)
+    for (int mt = 0; mt < MT16; ++mt)
 #pragma unroll
-      for (int e = 0; e < 16; ++e) acc[nt][mt][e] = 0.f;
+      for (int e = 0; e < 4; ++e) acc[nt][mt][e] = 0.f;
 
   const int nk = K / BK;
 #pragma unroll
@@ -178,56 +182,62 @@ gemm_bf16_mfma_kernel(const bf16_t *__restrict__ A, const bf16_t *__restrict__ W
     else if ((kStages >= 3 || kLate) && n >= 1) wait_vmcnt<kLoadsPerStage>();
     else wait_vmcnt<0>();
   };
-  // Fragment j of a k-step in the order the MFMAs below first need them: W 0, A 0..MT-1, W 1..
-  bf16x8 af[2][MT], wf[2][NT];
-  auto read_one = [&](const unsigned char *stage, int kk, int buf, int j) {
-    if (j == 0) wf[buf][0] = *reinterpret_cast<const bf16x8 *>(stage + w_base + frag_off[kk]);
-    else if (j <= MT) af[buf][j - 1] = *reinterpret_cast<const bf16x8 *>(stage + a_base + (j - 1) * 32 * kRowBytes + frag_off[kk]);
-    else wf[buf][j - MT] = *reinterpret_cast<const bf16x8 *>(stage + w_base + (j - MT) * 32 * kRowBytes + frag_off[kk]);
+  bf16x8 af[MT16], wf[NT16];                                 // operand fragments of ONE k-step (32 k)
+  auto read_a = [&](const unsigned char *stage, int kk, int mt) {
+    af[mt] = *reinterpret_cast<const bf16x8 *>(stage + a_base + mt * 16 * kRowBytes + frag_off[kk]);
+  };
+  auto read_w = [&](const unsigned char *stage, int kk, int nt) {
+    wf[nt] = *reinterpret_cast<const bf16x8 *>(stage + w_base + nt * 16 * kRowBytes + frag_off[kk]);
   };
 
-  // Software pipeline over k-steps (16 k each), written out in issue order and pinned with
+  // Software pipeline over k-steps (32 k each), written out in issue order and pinned with
   // sched_barrier after every MFMA: a wave issues in order, so whatever stands between two
-  // MFMAs must fit into the 32 cycles the first one keeps the matrix pipe busy.  After MFMA i
-  // of a k-step come at most one LDS read (fragment i of the NEXT k-step, double-buffered in
-  // registers) and the direct loads that fall to it (the refill of the ring slot freed by the
-  // last barrier, spread over the first KS-1 k-steps instead of one burst).  In the LAST k-step
-  // of stage kt the wave first waits for its own direct loads of stage kt+1 and passes the
-  // block's one barrier per stage; the fragments it then reads are the first ones of stage kt+1.
+  // MFMAs must fit into the cycles the first one keeps the matrix pipe busy.  A k-step runs its
+  // MFMAs n sub-tile by n sub-tile; each operand fragment is a single register set that is
+  // re-read from LDS for the NEXT k-step right after its last use in this one (W fragment nt
+  // after the last MFMA of pass nt, A fragment mt after MFMA (last pass, mt)), so the earliest
+  // reuse is a full pass of MFMAs later.  The direct loads that fall to a k-step follow one
+  // MFMA each.  In the LAST k-step of stage kt the wave, a few MFMAs in, waits for its own direct
+  // loads of stage kt+1 and for its outstanding LDS reads and passes the block's one barrier per
+  // stage; the fragments it reads after that are the first ones of stage kt+1.
   // A steady stage (one that still prefetches) has compile-time wait counts and no branches.
-  constexpr int kMfmaPerStep = MT * NT, kDsPerStep = MT + NT;
-  constexpr int kVmPerStep = (kLoadsPerStage + KS - 2) / (KS - 1);
-  constexpr int kDsPerMfma = (kDsPerStep + kMfmaPerStep - 1) / kMfmaPerStep;   // 1 except for the small-M shapes
+  constexpr int kMfmaPerStep = MT16 * NT16;
+  constexpr int kVmPerStep = KS > 1 ? (kLoadsPerStage + KS - 2) / (KS - 1) : kLoadsPerStage;
+  constexpr int kBarrierAt = MT16 - 1 < 4 ? MT16 - 1 : 4;   // MFMAs of the last k-step issued before the barrier
+  static_assert(!kLate || kLoadsPerStage <= kMfmaPerStep - kBarrierAt, "one refill load per MFMA after the barrier");
   wait_stages(min(kAhead - 1, nk - 1));
   __builtin_amdgcn_s_barrier();
 #pragma unroll
-  for (int j = 0; j < kDsPerStep; ++j) read_one(lds, 0, 0, j);
+  for (int nt = 0; nt < NT16; ++nt) read_w(lds, 0, nt);
+#pragma unroll
+  for (int mt = 0; mt < MT16; ++mt) read_a(lds, 0, mt);
   auto run_stage = [&](int kt, auto steady) {
     constexpr bool kSteady = decltype(steady)::value;
     const unsigned char *stage = lds + (kt % kStages) * kStage;
     const unsigned char *next = lds + ((kt + 1) % kStages) * kStage;
 #pragma unroll
     for (int kk = 0; kk < KS; ++kk) {
-      const int cur = kk & 1, nxt = cur ^ 1;
       const bool last = kk + 1 == KS;
       const bool more = !last || kSteady || kt + 1 < nk;     // is there a next k-step to read for
-      if (last && more) {
-        if (kSteady) wait_vmcnt<(kStages - 2) * kLoadsPerStage>();   // stage kt+1 has landed (my part of it)
-        else wait_stages(min(kStages - 2, nk - 2 - kt));
-        __builtin_amdgcn_s_waitcnt(0xc07f);                  // lgkmcnt(0): my reads of stage kt are done
-        // Raw barrier (no fence): every wave has waited for its own direct loads and LDS reads.
-        __builtin_amdgcn_s_barrier();
-      }
+      const unsigned char *src = last ? next : stage;
+      const int skk = last ? 0 : kk + 1;
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int i = 0; i < kMfmaPerStep; ++i) {
-        const int nt = i / MT, mt = i % MT;
-        acc[nt][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[cur][nt], af[cur][mt], acc[nt][mt], 0, 0, 0);
+        const int nt = i / MT16, mt = i % MT16;
+        if (last && more && i == kBarrierAt) {
+          if (kSteady) wait_vmcnt<(kStages - 2) * kLoadsPerStage>();   // stage kt+1 has landed (my part of it)
+          else wait_stages(min(kStages - 2, nk - 2 - kt));
+          __builtin_amdgcn_s_waitcnt(0xc07f);                // lgkmcnt(0): my reads of stage kt are done
+          // Raw barrier (no fence): every wave has waited for its own direct loads and LDS reads.
+          __builtin_amdgcn_s_barrier();
+          __builtin_amdgcn_sched_barrier(0);
+        }
+        acc[nt][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[nt], af[mt], acc[nt][mt], 0, 0, 0);
         __builtin_amdgcn_sched_barrier(0);
         if (more) {
-#pragma unroll
-          for (int q = 0; q < kDsPerMfma; ++q)
-            if (i * kDsPerMfma + q < kDsPerStep) read_one(last ? next : stage, last ? 0 : kk + 1, nxt, i * kDsPerMfma + q);
+          if (mt == MT16 - 1) read_w(src, skk, nt);
+          if (nt == NT16 - 1) read_a(src, skk, mt);
         }
         if (!kLate && kSteady && !last) {
 #pragma unroll
@@ -235,10 +245,8 @@ gemm_bf16_mfma_kernel(const bf16_t *__restrict__ A, const bf16_t *__restrict__ W
             if ((q * kMfmaPerStep) / kVmPerStep == i && kk * kVmPerStep + q < kLoadsPerStage)
               issue_one(kt + kStages - 1, kk * kVmPerStep + q);
         }
-        if (kLate && kSteady && last) {                      // slot kt % kStages was freed by the barrier above
-          static_assert(!kLate || kLoadsPerStage <= kMfmaPerStep, "one refill load per MFMA of the last k-step");
-          if (i < kLoadsPerStage) issue_one(kt + kStages, i);
-        }
+        if (kLate && kSteady && last && i >= kBarrierAt && i - kBarrierAt < kLoadsPerStage)
+          issue_one(kt + kStages, i - kBarrierAt);           // slot kt % kStages was freed by the barrier above
         __builtin_amdgcn_sched_barrier(0);
       }
     }
@@ -249,9 +257,8 @@ gemm_bf16_mfma_kernel(const bf16_t *__restrict__ A, const bf16_t *__restrict__ W
   for (; kt < nk; ++kt) run_stage(kt, std::false_type{});
 
   // ---- epilogue ----
-  // A lane holds, for sub-tile (nt, mt) and group i, the 4 consecutive columns
-  // nt*32 + 8*i + 4*(lane/32) + {0..3} of row mt*32 + lane%32: one row per lane, so a direct
-  // store would touch 32 rows with 8 bytes each.  Instead each wave turns 32 rows at a time
+  // A lane holds, for sub-tile (nt, mt), the 4 consecutive columns nt*16 + 4*(lane/16) + {0..3}
+  // of row mt*16 + lane%16, so a direct store would write 8-byte pieces.  Instead each wave turns 32 rows at a time
   // around through its own piece of the (now free) LDS ring and stores 16 bytes per lane with
   // consecutive lanes along a row (whole 128-byte lines).  Staging is bf16 except for the
   // residual epilogue, which stages float32 so that acc + residual is rounded once.
@@ -282,31 +289,33 @@ gemm_bf16_mfma_kernel(const bf16_t *__restrict__ A, const bf16_t *__restrict__ W
   unsigned char *my = lds + wave * (32 * kStride);
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt) {
-    unsigned char *wrow = my + fr * kStride;
-    if (EPI == kEpiSwiglu) {
+    // lane: row h*16 + lane%16 of the pass (h = 16-row half), 4 consecutive columns per n sub-tile
 #pragma unroll
-      for (int p = 0; p < NT / 2; ++p)
+    for (int h = 0; h < 2; ++h) {
+      unsigned char *wrow = my + (h * 16 + fr) * kStride;
+      const int m16 = 2 * mt + h;
+      if (EPI == kEpiSwiglu) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          float v[4];
+        for (int P = 0; P < NT16 / 4; ++P)
 #pragma unroll
-          for (int j = 0; j < 4; ++j) v[j] = silu_f(acc[2 * p][mt][4 * i + j]) * acc[2 * p + 1][mt][4 * i + j];
-          *reinterpret_cast<uint2 *>(wrow + (p * 32 + 8 * i + 4 * fh) * 2) =
-              make_uint2(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]));
-        }
-    } else {
+          for (int c = 0; c < 2; ++c) {                     // gate sub-tiles 4P, 4P+1; up sub-tiles 4P+2, 4P+3
+            float v[4];
 #pragma unroll
-      for (int nt = 0; nt < NT; ++nt)
+            for (int j = 0; j < 4; ++j) v[j] = silu_f(acc[4 * P + c][m16][j]) * acc[4 * P + 2 + c][m16][j];
+            *reinterpret_cast<uint2 *>(wrow + (P * 32 + c * 16 + 4 * fq) * 2) =
+                make_uint2(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]));
+          }
+      } else {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          const int col = nt * 32 + 8 * i + 4 * fh;
+        for (int nt = 0; nt < NT16; ++nt) {
+          const int col = nt * 16 + 4 * fq;
           if (EPI == kEpiResidual)
-            *reinterpret_cast<float4 *>(wrow + col * 4) = make_float4(acc[nt][mt][4 * i], acc[nt][mt][4 * i + 1],
-                                                                     acc[nt][mt][4 * i + 2], acc[nt][mt][4 * i + 3]);
+            *reinterpret_cast<float4 *>(wrow + col * 4) = make_float4(acc[nt][m16][0], acc[nt][m16][1], acc[nt][m16][2], acc[nt][m16][3]);
           else
-            *reinterpret_cast<uint2 *>(wrow + col * 2) = make_uint2(pack_bf16x2(acc[nt][mt][4 * i], acc[nt][mt][4 * i + 1]),
-                                                                   pack_bf16x2(acc[nt][mt][4 * i + 2], acc[nt][mt][4 * i + 3]));
+            *reinterpret_cast<uint2 *>(wrow + col * 2) = make_uint2(pack_bf16x2(acc[nt][m16][0], acc[nt][m16][1]),
+                                                                   pack_bf16x2(acc[nt][m16][2], acc[nt][m16][3]));
         }
+      }
     }
     if (EPI == kEpiQkvRope) {
       static_assert(EPI != kEpiQkvRope || ((WTN == 64 && WN % 2 == 0) || WTN == 128), "a head is one or two wave tiles wide");
@@ -420,37 +429,37 @@ pvf_status run(pvf_ctx *ctx, hipStream_t s, const void *A, const void *W, void *
   return PVF_OK;
 }
 
-struct TileCfg { int bm, bn, bk, stages; double eff; };
-constexpr int kNumCfg = 12;
+struct TileCfg { int bm, bn, bk, stages; double eff; bool plain_only; };
+constexpr int kNumCfg = 9;
+// Every shape runs two waves per SIMD (8 waves with one workgroup per CU, or 4 waves with two):
+// a single wave cannot keep the matrix pipe busy with 16x16x32 MFMAs and the LDS reads between them.
+// plain_only: wave tiles 32 columns wide, which the SwiGLU and rotary epilogues cannot pair up.
 constexpr TileCfg kCfg[kNumCfg] = {
-    {256, 256, 32, 4, 1.00},   // 8 waves
-    {128, 256, 64, 3, 0.85}, {256, 128, 64, 3, 0.85}, {128, 128, 64, 4, 0.80},
-    {256, 256, 32, 4, 0.0},    // shape 0 with 4 waves (only when forced)
-    {192, 256, 32, 4, 0.97},   // fills the chip when M / 256 leaves many CUs idle
-    {64, 64, 64, 5, 0.0},      // few rows (window forward of the K/V-cached rounds): the GEMM streams the weights,
-    {64, 128, 64, 3, 0.0},     // so many small workgroups with deep rings; chosen by pick_config for M <= 320
-    {160, 256, 64, 3, 0.90},   // 2560 rows = 16 tile rows: with N = 4096 exactly one tile per CU
-    {96, 256, 64, 3, 0.85},    // the same for 1536 rows
-    {256, 256, 64, 2, 1.07},   // shape 0 with 128-byte rows in a ring of two stages: half as many L2 requests
-    {256, 256, 64, 2, 0.0}};   // the same with 4 waves
+    {256, 256, 64, 2, 1.00, false},   // the wide layers
+    {128, 256, 64, 3, 0.85, false}, {256, 128, 64, 3, 0.85, false},
+    {128, 128, 64, 2, 0.75, false},   // 4 waves, two workgroups per CU
+    {192, 256, 64, 2, 0.90, false},   // fills the chip when M / 256 leaves many CUs idle
+    {320, 128, 64, 2, 0.90, true},    // 2560 rows = 8 tile rows: with N = 4096 exactly one tile per CU
+    {64, 64, 64, 5, 0.0, true},       // few rows (window forward of the K/V-cached rounds): the GEMM streams the weights,
+    {64, 128, 64, 3, 0.0, false},     // so many small workgroups with deep rings; chosen by pick_config for M <= 384
+    {192, 128, 64, 3, 0.85, true}};   // 1536 rows = 8 tile rows: with N = 4096 one tile per CU
 
 template <int EPI>
 pvf_status run_cfg(pvf_ctx *ctx, hipStream_t s, int cfg, const void *A, const void *W, void *C,
                    const void *Res, int M, int N, int K, const RopeArgs &ra = RopeArgs{}) {
+  constexpr bool kPlain = EPI != kEpiSwiglu && EPI != kEpiQkvRope;
   switch (cfg) {
-    case 0: return run<EPI, 256, 256, 32, 4, 2, 4>(ctx, s, A, W, C, Res, M, N, K, ra);
-    case 1: return run<EPI, 128, 256, 64, 3, 2, 2>(ctx, s, A, W, C, Res, M, N, K, ra);
-    case 2: return run<EPI, 256, 128, 64, 3, 2, 2>(ctx, s, A, W, C, Res, M, N, K, ra);
-    case 3: return run<EPI, 128, 128, 64, 4, 2, 2>(ctx, s, A, W, C, Res, M, N, K, ra);
-    case 4: return run<EPI, 256, 256, 32, 4, 2, 2>(ctx, s, A, W, C, Res, M, N, K, ra);
-    case 5: return run<EPI, 192, 256, 32, 4, 2, 2>(ctx, s, A, W, C, Res, M, N, K, ra);
-    case 6: if constexpr (EPI != kEpiSwiglu && EPI != kEpiQkvRope) return run<EPI, 64, 64, 64, 5, 2, 2>(ctx, s, A, W, C, Res, M, N, K, ra);
+    case 0: return run<EPI, 256, 256, 64, 2, 2, 4>(ctx, s, A, W, C, Res, M, N, K, ra);
+    case 1: return run<EPI, 128, 256, 64, 3, 2, 4>(ctx, s, A, W, C, Res, M, N, K, ra);
+    case 2: return run<EPI, 256, 128, 64, 3, 4, 2>(ctx, s, A, W, C, Res, M, N, K, ra);
+    case 4: return run<EPI, 192, 256, 64, 2, 2, 4>(ctx, s, A, W, C, Res, M, N, K, ra);
+    case 5: if constexpr (kPlain) return run<EPI, 320, 128, 64, 2, 2, 4>(ctx, s, A, W, C, Res, M, N, K, ra); break;
+    case 6: if constexpr (kPlain) return run<EPI, 64, 64, 64, 5, 2, 2>(ctx, s, A, W, C, Res, M, N, K, ra); break;
     case 7: return run<EPI, 64, 128, 64, 3, 2, 2>(ctx, s, A, W, C, Res, M, N, K, ra);
-    case 8: return run<EPI, 160, 256, 64, 3, 1, 4>(ctx, s, A, W, C, Res, M, N, K, ra);
-    case 9: return run<EPI, 96, 256, 64, 3, 1, 4>(ctx, s, A, W, C, Res, M, N, K, ra);
-    case 10: return run<EPI, 256, 256, 64, 2, 2, 4>(ctx, s, A, W, C, Res, M, N, K, ra);
-    default: return run<EPI, 256, 256, 64, 2, 2, 2>(ctx, s, A, W, C, Res, M, N, K, ra);
+    case 8: if constexpr (kPlain) return run<EPI, 192, 128, 64, 3, 2, 4>(ctx, s, A, W, C, Res, M, N, K, ra); break;
+    default: break;
   }
+  return run<EPI, 128, 128, 64, 2, 2, 2>(ctx, s, A, W, C, Res, M, N, K, ra);
 }
 
 // Tile shape: the one with the least estimated time = rounds of workgroups over the 256 CUs
@@ -459,20 +468,21 @@ pvf_status run_cfg(pvf_ctx *ctx, hipStream_t s, int cfg, const void *A, const vo
 // PVF_GEMM_TILE=<n> in the environment forces shape n (for tuning runs).
 int pick_config(GemmEpilogue epi, int M, int N, int K) {
   static const int forced = [] { const char *e = getenv("PVF_GEMM_TILE"); return (e && e[0]) ? atoi(e) : -1; }();
+  const bool plain = epi != kEpiSwiglu && epi != kEpiQkvRope;
   // Few rows: the launch streams the weight matrix once and is bound by HBM, not by the MFMAs.
   // Many small workgroups with deep LDS rings keep more bytes in flight (measured on the layer
   // shapes: 3.2x faster than the large tiles at M = 64, 2x at M = 320).
   // The output head (N = vocabulary) has enough tiles to fill the chip at any M > 64 and goes by the
   // cost model below.
-  if (forced < 0 && M <= 384 && K % 64 == 0 && (M <= 64 || N <= 32768)) {
-    if (epi != kEpiSwiglu && epi != kEpiQkvRope && M <= 128 && N % 64 == 0) return 6;
+  if (forced < 0 && M <= 384 && (M <= 64 || N <= 32768)) {
+    if (plain && M <= 128 && N % 64 == 0) return 6;
     if (N % (epi == kEpiSwiglu ? 64 : 128) == 0) return 7;
   }
   int best = -1;
   double best_t = 0;
   for (int c = 0; c < kNumCfg; ++c) {
     const int ncols = (epi == kEpiSwiglu) ? kCfg[c].bn / 2 : kCfg[c].bn;
-    if (N % ncols != 0 || K % kCfg[c].bk != 0) continue;
+    if (N % ncols != 0 || K % kCfg[c].bk != 0 || (kCfg[c].plain_only && !plain)) continue;
     if (forced == c) return c;
     if (kCfg[c].eff <= 0.0) continue;
     const int64_t tiles = (int64_t)((M + kCfg[c].bm - 1) / kCfg[c].bm) * (N / ncols);
@@ -491,8 +501,7 @@ bool gemm_mfma_supported(int dtype, GemmEpilogue epi, int M, int N, int K);
 bool gemm_mfma_qkv_rope_supported(int dtype, int M, int N, int K, int T, int H) {
   if (!gemm_mfma_supported(dtype, kEpiStore, M, N, K)) return false;
   if (N != 3 * H * 128 || H % 2 != 0 || T % 32 != 0 || M % T != 0) return false;
-  const int cfg = pick_config(kEpiQkvRope, M, N, K);
-  return cfg >= 0 && cfg != 6;
+  return pick_config(kEpiQkvRope, M, N, K) >= 0;
 }
 
 pvf_status launch_gemm_mfma_qkv_rope(pvf_ctx *ctx, hipStream_t s, const void *A, const void *W, void *qkv,
@@ -500,7 +509,7 @@ pvf_status launch_gemm_mfma_qkv_rope(pvf_ctx *ctx, hipStream_t s, const void *A,
   const uintptr_t al = (uintptr_t)A | (uintptr_t)W | (uintptr_t)qkv | (uintptr_t)vt;
   PVF_REQUIRE(ctx, (al & 15u) == 0, PVF_EINVAL, "gemm_mfma: operands must be 16-byte aligned");
   const int cfg = pick_config(kEpiQkvRope, M, N, K);
-  PVF_REQUIRE(ctx, cfg >= 0 && cfg != 6, PVF_ESHAPE, "gemm_mfma: no tile shape with a rotary epilogue for N=%d", N);
+  PVF_REQUIRE(ctx, cfg >= 0, PVF_ESHAPE, "gemm_mfma: no tile shape with a rotary epilogue for N=%d", N);
   RopeArgs ra;
   ra.cos_sin = cos_sin; ra.vt = (bf16_t *)vt; ra.T = T; ra.H = H;
   return run_cfg<kEpiQkvRope>(ctx, s, cfg, A, W, qkv, nullptr, M, N, K, ra);
