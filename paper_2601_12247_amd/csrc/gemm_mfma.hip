@@ -182,41 +182,49 @@ gemm_bf16_mfma_kernel(const bf16_t *__restrict__ A, const bf16_t *__restrict__ W
     else if ((kStages >= 3 || kLate) && n >= 1) wait_vmcnt<kLoadsPerStage>();
     else wait_vmcnt<0>();
   };
-  bf16x8 af[MT16], wf[NT16];                                 // operand fragments of ONE k-step (32 k)
-  auto read_a = [&](const unsigned char *stage, int kk, int mt) {
-    af[mt] = *reinterpret_cast<const bf16x8 *>(stage + a_base + mt * 16 * kRowBytes + frag_off[kk]);
+  // Operand fragments of a k-step (32 k).  The A fragments and the W fragment of the last pass
+  // are double-buffered in registers; the other W fragments are single register sets that are
+  // re-read for the next k-step right after the pass that used them.
+  static_assert(KS % 2 == 0, "the register double buffer alternates with the k-step inside a stage");
+  bf16x8 af[2][MT16], wf[NT16 - 1], wl[2];
+  auto read_a = [&](const unsigned char *stage, int kk, int buf, int mt) {
+    af[buf][mt] = *reinterpret_cast<const bf16x8 *>(stage + a_base + mt * 16 * kRowBytes + frag_off[kk]);
   };
-  auto read_w = [&](const unsigned char *stage, int kk, int nt) {
-    wf[nt] = *reinterpret_cast<const bf16x8 *>(stage + w_base + nt * 16 * kRowBytes + frag_off[kk]);
+  auto read_w = [&](const unsigned char *stage, int kk, int buf, int nt) {
+    const bf16x8 v = *reinterpret_cast<const bf16x8 *>(stage + w_base + nt * 16 * kRowBytes + frag_off[kk]);
+    if (nt == NT16 - 1) wl[buf] = v; else wf[nt] = v;
   };
 
-  // Software pipeline over k-steps (32 k each), written out in issue order and pinned with
-  // sched_barrier after every MFMA: a wave issues in order, so whatever stands between two
-  // MFMAs must fit into the cycles the first one keeps the matrix pipe busy.  A k-step runs its
-  // MFMAs n sub-tile by n sub-tile; each operand fragment is a single register set that is
-  // re-read from LDS for the NEXT k-step right after its last use in this one (W fragment nt
-  // after the last MFMA of pass nt, A fragment mt after MFMA (last pass, mt)), so the earliest
-  // reuse is a full pass of MFMAs later.  The direct loads that fall to a k-step follow one
-  // MFMA each.  In the LAST k-step of stage kt the wave, a few MFMAs in, waits for its own direct
-  // loads of stage kt+1 and for its outstanding LDS reads and passes the block's one barrier per
-  // stage; the fragments it reads after that are the first ones of stage kt+1.
+  // Software pipeline over k-steps, written out in issue order and pinned with sched_barrier
+  // after every MFMA: a wave issues in order, so whatever stands between two MFMAs must fit into
+  // the cycles the first one keeps the matrix pipe busy.  A k-step runs its MFMAs n sub-tile by
+  // n sub-tile (a "pass" = one W fragment against all A fragments).  The LDS reads for the NEXT
+  // k-step follow single MFMAs and are all issued before the last pass starts, so a k-step never
+  // begins by waiting for LDS.  The direct loads that fall to a k-step follow one MFMA each.
+  // In the LAST k-step of stage kt the wave, kBarrierAt MFMAs in, waits for its own direct loads
+  // of stage kt+1 and passes the block's one barrier per stage (its LDS reads of stage kt were
+  // issued a pass or more ago); the fragments it reads after that are the first ones of stage kt+1.
   // A steady stage (one that still prefetches) has compile-time wait counts and no branches.
   constexpr int kMfmaPerStep = MT16 * NT16;
   constexpr int kVmPerStep = KS > 1 ? (kLoadsPerStage + KS - 2) / (KS - 1) : kLoadsPerStage;
   constexpr int kBarrierAt = MT16 - 1 < 4 ? MT16 - 1 : 4;   // MFMAs of the last k-step issued before the barrier
+  // the A reads are spread over MFMAs (kBarrierAt, kReadEnd): up to the start of the last pass
+  constexpr int kReadEnd = (NT16 - 1) * MT16 > kBarrierAt + 2 ? (NT16 - 1) * MT16 : kBarrierAt + 2;
   static_assert(!kLate || kLoadsPerStage <= kMfmaPerStep - kBarrierAt, "one refill load per MFMA after the barrier");
+  static_assert(kReadEnd <= kMfmaPerStep, "the A reads fit into the k-step");
   wait_stages(min(kAhead - 1, nk - 1));
   __builtin_amdgcn_s_barrier();
 #pragma unroll
-  for (int nt = 0; nt < NT16; ++nt) read_w(lds, 0, nt);
+  for (int nt = 0; nt < NT16; ++nt) read_w(lds, 0, 0, nt);
 #pragma unroll
-  for (int mt = 0; mt < MT16; ++mt) read_a(lds, 0, mt);
+  for (int mt = 0; mt < MT16; ++mt) read_a(lds, 0, 0, mt);
   auto run_stage = [&](int kt, auto steady) {
     constexpr bool kSteady = decltype(steady)::value;
     const unsigned char *stage = lds + (kt % kStages) * kStage;
     const unsigned char *next = lds + ((kt + 1) % kStages) * kStage;
 #pragma unroll
     for (int kk = 0; kk < KS; ++kk) {
+      const int cur = kk & 1, nxt = cur ^ 1;
       const bool last = kk + 1 == KS;
       const bool more = !last || kSteady || kt + 1 < nk;     // is there a next k-step to read for
       const unsigned char *src = last ? next : stage;
@@ -233,11 +241,14 @@ gemm_bf16_mfma_kernel(const bf16_t *__restrict__ A, const bf16_t *__restrict__ W
           __builtin_amdgcn_s_barrier();
           __builtin_amdgcn_sched_barrier(0);
         }
-        acc[nt][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[nt], af[mt], acc[nt][mt], 0, 0, 0);
+        acc[nt][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(nt == NT16 - 1 ? wl[cur] : wf[nt], af[cur][mt], acc[nt][mt], 0, 0, 0);
         __builtin_amdgcn_sched_barrier(0);
         if (more) {
-          if (mt == MT16 - 1) read_w(src, skk, nt);
-          if (nt == NT16 - 1) read_a(src, skk, mt);
+          if (i == kBarrierAt) read_w(src, skk, nxt, NT16 - 1);
+#pragma unroll
+          for (int m2 = 0; m2 < MT16; ++m2)
+            if (i == kBarrierAt + 1 + (m2 * (kReadEnd - kBarrierAt - 1)) / MT16) read_a(src, skk, nxt, m2);
+          if (mt == MT16 - 1 && nt < NT16 - 1) read_w(src, skk, nxt, nt);
         }
         if (!kLate && kSteady && !last) {
 #pragma unroll
