@@ -298,8 +298,21 @@ gemm_bf16_mfma_kernel(const bf16_t *__restrict__ A, const bf16_t *__restrict__ W
   }
   __syncthreads();                                                   // every wave is done with the ring
   unsigned char *my = lds + wave * (32 * kStride);
+  const int rope_third = EPI == kEpiQkvRope ? (tile_n * BN) / (N_out / 3) : 2;   // 0 = q, 1 = k, 2 = v (uniform per workgroup)
+  const int col_in_head = (out_col0 + rd_col) & 127;
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt) {
+    // rotary epilogue: the cos / sin of this pass's rows are requested before the staging, which hides their latency
+    float4 csr[EPI == kEpiQkvRope ? kRowIters : 1][4];
+    if (EPI == kEpiQkvRope && rope_third < 2) {
+#pragma unroll
+      for (int j = 0; j < kRowIters; ++j) {
+        const int m = m0 + wm * WTM + mt * 32 + j * kRowsPerInstr + rd_row;
+        const float4 *cs4 = reinterpret_cast<const float4 *>(ra.cos_sin + (int64_t)(min(m, M - 1) % ra.T) * 64 + (col_in_head & 63));
+#pragma unroll
+        for (int e = 0; e < 4; ++e) csr[j][e] = cs4[e];
+      }
+    }
     // lane: row h*16 + lane%16 of the pass (h = 16-row half), 4 consecutive columns per n sub-tile
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
@@ -331,11 +344,9 @@ gemm_bf16_mfma_kernel(const bf16_t *__restrict__ A, const bf16_t *__restrict__ W
     if (EPI == kEpiQkvRope) {
       static_assert(EPI != kEpiQkvRope || ((WTN == 64 && WN % 2 == 0) || WTN == 128), "a head is one or two wave tiles wide");
       const int d_model = N_out / 3;
-      const int third = (tile_n * BN) / d_model;                     // 0 = q, 1 = k, 2 = v (uniform per workgroup)
       const int m_base = m0 + wm * WTM + mt * 32;
       if (WTN == 64) __syncthreads();                                // the partner wave's half of the head is staged
-      if (third < 2) {
-        const int col_in_head = (out_col0 + rd_col) & 127;
+      if (rope_third < 2) {
         const bool upper = col_in_head >= 64;
         const unsigned char *partner = (WTN == 64) ? lds + (wave ^ 1) * (32 * kStride) + rd_col * 2
                                                    : my + (rd_col ^ 64) * 2;
@@ -346,12 +357,12 @@ gemm_bf16_mfma_kernel(const bf16_t *__restrict__ A, const bf16_t *__restrict__ W
           const uint4 own = *reinterpret_cast<const uint4 *>(my + r * kStride + rd_col * 2);
           const uint4 oth = *reinterpret_cast<const uint4 *>(partner + r * kStride);
           if (m < M) {
-            const float2 *cs = ra.cos_sin + (int64_t)(m % ra.T) * 64 + (col_in_head & 63);
             const uint32_t ow[4] = {own.x, own.y, own.z, own.w}, pw[4] = {oth.x, oth.y, oth.z, oth.w};
             uint32_t res[4];
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-              const float2 c0 = cs[2 * e], c1 = cs[2 * e + 1];
+              const float4 c4 = csr[EPI == kEpiQkvRope ? j : 0][e];
+              const float2 c0 = make_float2(c4.x, c4.y), c1 = make_float2(c4.z, c4.w);
               const float a0 = __uint_as_float(ow[e] << 16), a1 = __uint_as_float(ow[e] & 0xffff0000u);
               const float b0 = __uint_as_float(pw[e] << 16), b1 = __uint_as_float(pw[e] & 0xffff0000u);
               // lower half: x*cos - partner*sin; upper half: x*cos + partner*sin
