@@ -453,18 +453,18 @@ pvf_status run(pvf_ctx *ctx, hipStream_t s, const void *A, const void *W, void *
 
 struct TileCfg { int bm, bn, bk, stages; double eff; bool plain_only; };
 constexpr int kNumCfg = 9;
-// Every shape runs two waves per SIMD (8 waves with one workgroup per CU, or 4 waves with two):
+// Every shape for many rows runs 8 waves, two per SIMD (the two small ones 4 waves, two workgroups per CU):
 // a single wave cannot keep the matrix pipe busy with 16x16x32 MFMAs and the LDS reads between them.
 // plain_only: wave tiles 32 columns wide, which the SwiGLU and rotary epilogues cannot pair up.
 constexpr TileCfg kCfg[kNumCfg] = {
     {256, 256, 64, 2, 1.00, false},   // the wide layers
-    {128, 256, 64, 3, 0.85, false}, {256, 128, 64, 3, 0.85, false},
-    {128, 128, 64, 2, 0.75, false},   // 4 waves, two workgroups per CU
-    {192, 256, 64, 2, 0.90, false},   // fills the chip when M / 256 leaves many CUs idle
-    {320, 128, 64, 2, 0.90, true},    // 2560 rows = 8 tile rows: with N = 4096 exactly one tile per CU
+    {128, 256, 64, 3, 0.89, false}, {256, 128, 64, 3, 0.885, false},
+    {128, 128, 64, 3, 0.70, false},   // launches of a single round of tiles: the smallest area finishes first
+    {192, 256, 64, 2, 0.93, false},   // fills the chip when M / 256 leaves many CUs idle
+    {320, 128, 64, 2, 0.78, true},    // 2560 rows = 8 tile rows: with N = 4096 exactly one tile per CU
     {64, 64, 64, 5, 0.0, true},       // few rows (window forward of the K/V-cached rounds): the GEMM streams the weights,
     {64, 128, 64, 3, 0.0, false},     // so many small workgroups with deep rings; chosen by pick_config for M <= 384
-    {192, 128, 64, 3, 0.85, true}};   // 1536 rows = 8 tile rows: with N = 4096 one tile per CU
+    {192, 128, 64, 3, 0.86, true}};   // 1536 rows = 8 tile rows: with N = 4096 one tile per CU
 
 template <int EPI>
 pvf_status run_cfg(pvf_ctx *ctx, hipStream_t s, int cfg, const void *A, const void *W, void *C,
@@ -481,7 +481,7 @@ pvf_status run_cfg(pvf_ctx *ctx, hipStream_t s, int cfg, const void *A, const vo
     case 8: if constexpr (kPlain) return run<EPI, 192, 128, 64, 3, 2, 4>(ctx, s, A, W, C, Res, M, N, K, ra); break;
     default: break;
   }
-  return run<EPI, 128, 128, 64, 2, 2, 2>(ctx, s, A, W, C, Res, M, N, K, ra);
+  return run<EPI, 128, 128, 64, 3, 4, 2>(ctx, s, A, W, C, Res, M, N, K, ra);
 }
 
 // Tile shape: the one with the least estimated time = rounds of workgroups over the 256 CUs
