@@ -441,9 +441,11 @@ pvf_status run(pvf_ctx *ctx, hipStream_t s, const void *A, const void *W, void *
   const int tiles_n = (EPI == kEpiSwiglu) ? N_out / (BN / 2) : N_out / BN;
   const int total = tiles_m * tiles_n;
   const int grid = 8 * ((total + 7) / 8);
-  // bands of at most 8 tile rows, all of (nearly) the same height: the 32 workgroups that run
-  // together on an XCD then cover a patch close to 8 x 4 tiles in every band
-  const int n_bands = (tiles_m + 7) / 8;
+  // bands of at most kBand tile rows, all of (nearly) the same height: the 32 workgroups that run
+  // together on an XCD then cover a patch of kBand x 32/kBand tiles in every band, whose operand rows
+  // that XCD's L2 fetches once.  The patch that fetches least has rows : columns = BN : BM.
+  constexpr int kBand = BM > BN ? 4 : 8;
+  const int n_bands = (tiles_m + kBand - 1) / kBand;
   const int group_m = (tiles_m + n_bands - 1) / n_bands;
   gemm_bf16_mfma_kernel<EPI, BM, BN, BK, ST, WM, WN><<<grid, 64 * WM * WN, kLdsBytes, s>>>(
       (const bf16_t *)A, (const bf16_t *)W, (bf16_t *)C, (const bf16_t *)Res, M, N_out, K, tiles_m, tiles_n, group_m, ra);
