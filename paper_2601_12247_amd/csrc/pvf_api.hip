@@ -290,7 +290,7 @@ static pvf_status forward_impl(pvf_ctx *c, hipStream_t s, const int32_t *tokens,
       // the QKV projection rotates q, k and writes the key-contiguous v in its epilogue
       {
         ProfScope ps(c, s, PVF_PROF_GEMM, 2.0 * M * (double)(3 * d) * d,
-                     (double)c->esize * ((double)M * d + 3.0 * d * d + (double)M * 3 * d));
+                     (double)c->esize * ((double)M * d + 3.0 * d * d + (double)M * 3 * d + (double)M * d));   // + the key-contiguous v
         RUN(launch_gemm_mfma_qkv_rope(c, s, c->xn, c->wqkv[l], c->qkv, c->vt, c->cos_sin, M, 3 * d, d, T, H));
       }
       ProfScope ps(c, s, PVF_PROF_ATTENTION, 4.0 * S * (double)T * T * d, 0.0);
