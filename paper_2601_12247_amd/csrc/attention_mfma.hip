@@ -116,7 +116,14 @@ attention_mfma_kernel(const bf16_t *__restrict__ qkv, const bf16_t *__restrict__
   for (int t = 0; t < 4; ++t)
 #pragma unroll
     for (int e = 0; e < 16; ++e) o[t][e] = 0.f;
-  float m_run = -INFINITY, l_run = 0.f;
+  float m_run = -INFINITY;
+  floatx16 ol;                                               // ol[0] in lanes 0..31: running sum of P for query lane
+#pragma unroll
+  for (int e = 0; e < 16; ++e) ol[e] = 0.f;
+  const floatx16 kZero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  bf16x8 ones;                                               // "A" operand with row 0 = 1, rows 1..31 = 0
+#pragma unroll
+  for (int e = 0; e < 8; ++e) ones[e] = (bf16_t)(fr == 0 ? 1.0f : 0.0f);
   const float c = kLog2e / sqrtf((float)DH);
 
   const int nk = T / TK;
@@ -131,16 +138,13 @@ attention_mfma_kernel(const bf16_t *__restrict__ qkv, const bf16_t *__restrict__
     // ---- S^T = K Q^T : 2 key sub-tiles x 8 k-steps ----
     floatx16 s[2];
 #pragma unroll
-    for (int t = 0; t < 2; ++t)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) s[t][e] = 0.f;
-#pragma unroll
     for (int ks = 0; ks < 8; ++ks) {
 #pragma unroll
       for (int t = 0; t < 2; ++t) {
         const int key = t * 32 + fr;
         const bf16x8 kf = *reinterpret_cast<const bf16x8 *>(ks_ + key * 256 + (((ks * 2 + fh) ^ (key & 15)) << 4));
-        s[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], s[t], 0, 0, 0);
+        // the first k-step starts from a constant zero accumulator: no registers to clear per tile
+        s[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], ks == 0 ? kZero16 : s[t], 0, 0, 0);
       }
     }
     // ---- online softmax for this lane's query ----
@@ -153,7 +157,6 @@ attention_mfma_kernel(const bf16_t *__restrict__ qkv, const bf16_t *__restrict__
     const float m_new = fmaxf(m_run, mx);
     const float alpha = fast_exp2((m_run - m_new) * c);      // first tile: exp2(-inf) = 0
     const float nmc = -m_new * c;
-    float psum = 0.f;
     bf16x8 pf[4];                                            // "B" operand of the 4 key k-steps
 #pragma unroll
     for (int t = 0; t < 2; ++t)
@@ -161,18 +164,15 @@ attention_mfma_kernel(const bf16_t *__restrict__ qkv, const bf16_t *__restrict__
       for (int u = 0; u < 2; ++u)                            // k-step u of sub-tile t: register groups 2u, 2u+1
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
-          const float p = fast_exp2(fmaf(s[t][8 * u + e], c, nmc));
-          psum += p;
-          pf[2 * t + u][e] = (bf16_t)p;
+          pf[2 * t + u][e] = (bf16_t)fast_exp2(fmaf(s[t][8 * u + e], c, nmc));
         }
-    psum += __shfl_xor(psum, 32, 64);
-    l_run = l_run * alpha + psum;
     m_run = m_new;
     if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
 #pragma unroll
       for (int t = 0; t < 4; ++t)
 #pragma unroll
         for (int e = 0; e < 16; ++e) o[t][e] *= alpha;
+      ol[0] *= alpha;
     }
     // ---- O^T += V^T P^T : 4 d tiles x 4 key k-steps.  k slot (fh, e) of k-step ks2 is key
     //      16*ks2 + 4*fh + e (e < 4) or 16*ks2 + 8 + 4*fh + (e - 4): the order P came out in ----
@@ -182,14 +182,15 @@ attention_mfma_kernel(const bf16_t *__restrict__ qkv, const bf16_t *__restrict__
       for (int t = 0; t < 4; ++t) {
         const int vr = t * 32 + fr;
         const int swz = (vr >> 1) & 7;
-        const unsigned char *rowp = vs_ + vr * 128 + fh * 8;
-        const bf16x4 lo = *reinterpret_cast<const bf16x4 *>(rowp + (((2 * ks2) ^ swz) << 4));
-        const bf16x4 hi = *reinterpret_cast<const bf16x4 *>(rowp + (((2 * ks2 + 1) ^ swz) << 4));
-        const bf16x8 vf = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+        // vt stores each group of 16 keys as {0-3, 8-11 | 4-7, 12-15}: chunk 2*ks2 + fh is this lane's 8 keys
+        const bf16x8 vf = *reinterpret_cast<const bf16x8 *>(vs_ + vr * 128 + (((2 * ks2 + fh) ^ swz) << 4));
         o[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[ks2], o[t], 0, 0, 0);
       }
+      // row sums of P on the matrix pipe (a "V^T" row of ones): the vector ALU is the busier unit here
+      ol = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ones, pf[ks2], ol, 0, 0, 0);
     }
   }
+  const float l_run = __shfl(ol[0], fr, 64);                 // row 0 of that product: lane q % 32, register 0
 
   // ---- out[q][head*128 + d]: lane holds 4 consecutive d per accumulator group ----
   const int q = q0 + wave * 32 + fr;
@@ -208,8 +209,14 @@ attention_mfma_kernel(const bf16_t *__restrict__ qkv, const bf16_t *__restrict__
   }
 }
 
+// Position of key t inside a key-contiguous vt row: bits 2 and 3 of t are swapped, so that every
+// group of 16 keys is stored as {0-3, 8-11 | 4-7, 12-15}.  The 8 keys that one lane of the
+// attention kernel feeds into a k-step of the P V product (the order in which the S^T accumulators
+// hold them) are then one 16-byte chunk.
+__device__ __forceinline__ int vt_pos(int t) { return (t & ~12) | ((t & 4) << 1) | ((t & 8) >> 1); }
+
 // Rotary embedding of q and k in place (pair (i, i + 64) of each head) and the key-contiguous
-// copy of v:  vt[canvas][head][d][t] = v[canvas*T + t][head*128 + d].  One block = 64 positions
+// copy of v:  vt[canvas][head][d][vt_pos(t)] = v[canvas*T + t][head*128 + d].  One block = 64 positions
 // of one (canvas, head).
 __global__ void __launch_bounds__(256)
 rope_vt_kernel(bf16_t *__restrict__ qkv, bf16_t *__restrict__ vt, int T, int H,
@@ -237,7 +244,7 @@ rope_vt_kernel(bf16_t *__restrict__ qkv, bf16_t *__restrict__ vt, int T, int H,
   bf16_t *vb = vt + ((int64_t)seq * H + head) * DH * T + t0;
   for (int idx = tid; idx < DH * 64; idx += 256) {
     const int tt = idx & 63, dd = idx >> 6;
-    vb[(int64_t)dd * T + tt] = tile[dd][tt];
+    vb[(int64_t)dd * T + vt_pos(tt)] = tile[dd][tt];
   }
 }
 
@@ -270,17 +277,17 @@ rope_vt_rows_kernel(bf16_t *__restrict__ qkv, bf16_t *__restrict__ vt, const int
   bf16_t *vb = vt + ((int64_t)seq * H + head) * DH * R + r0;
   for (int idx = tid; idx < DH * 64; idx += 256) {
     const int rr = idx & 63, dd = idx >> 6;
-    vb[(int64_t)dd * R + rr] = tile[dd][rr];
+    vb[(int64_t)dd * R + vt_pos(rr)] = tile[dd][rr];
   }
 }
 
 }  // namespace
 
-// Window attention on the matrix cores needs whole 64-row blocks of window rows and 8-key
-// chunks that lie entirely inside or outside the window.
+// Window attention on the matrix cores needs whole 64-row blocks of window rows and 16-key
+// groups (the unit of the vt key order) that lie entirely inside or outside the window.
 bool attention_window_mfma_supported(int dtype, int T, int d_head, int R, int block_len, int prompt_len) {
-  return dtype == PVF_BF16 && d_head == DH && T >= TK && T % TK == 0 && R % 64 == 0 && block_len % 8 == 0 &&
-         prompt_len % 8 == 0;
+  return dtype == PVF_BF16 && d_head == DH && T >= TK && T % TK == 0 && R % 64 == 0 && block_len % 16 == 0 &&
+         prompt_len % 16 == 0;
 }
 
 pvf_status launch_rope_vt_rows(pvf_ctx *ctx, hipStream_t s, void *qkv, void *vt, const int32_t *row_pos,

@@ -75,8 +75,8 @@ constexpr int waves_per_simd(int lds_bytes, int waves) { return (lds_bytes <= 80
 // kEpiQkvRope: the GEMM is the QKV projection of canvases of T tokens (d_head = 128, N = 3 * H * 128).
 // Its epilogue rotates the q and k thirds (rotary embedding, pair (i, i + 64) of each head, angle
 // of canvas position row % T from the cos_sin table [T][64]) before storing them, and writes the
-// v third a second time key-contiguous, vt[canvas][head][d][t], the layout the attention kernel
-// reads its values in.
+// v third a second time key-contiguous, vt[canvas][head][d][t'] with bits 2 and 3 of t swapped in t'
+// (each 16 keys stored as {0-3, 8-11 | 4-7, 12-15}), the layout the attention kernel reads its values in.
 struct RopeArgs {
   const float2 *cos_sin;
   bf16_t *vt;
@@ -397,7 +397,10 @@ gemm_bf16_mfma_kernel(const bf16_t *__restrict__ A, const bf16_t *__restrict__ W
             const int head = (vcol0 + c) >> 7, dcol = (vcol0 + c) & 127;
             uint4 *dst = reinterpret_cast<uint4 *>(ra.vt + (((int64_t)seq * ra.H + head) * 128 + dcol) * ra.T + t0);
 #pragma unroll
-            for (int q4 = 0; q4 < 4; ++q4) dst[q4] = make_uint4(w[4 * q4], w[4 * q4 + 1], w[4 * q4 + 2], w[4 * q4 + 3]);
+            for (int g = 0; g < 2; ++g) {                             // each 16 keys stored as {0-3, 8-11 | 4-7, 12-15}
+              dst[2 * g] = make_uint4(w[8 * g], w[8 * g + 1], w[8 * g + 4], w[8 * g + 5]);
+              dst[2 * g + 1] = make_uint4(w[8 * g + 2], w[8 * g + 3], w[8 * g + 6], w[8 * g + 7]);
+            }
           }
         }
       }
