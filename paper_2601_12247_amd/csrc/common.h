@@ -139,7 +139,7 @@ pvf_status launch_gather_rows(pvf_ctx *ctx, hipStream_t s, int dtype, const void
                               const int32_t *row_pos, int S, int T, int R, int d, void *out);
 pvf_status launch_rope(pvf_ctx *ctx, hipStream_t s, int dtype, void *qkv, int M, int T,
                        int n_heads, int d_head, const float2 *cos_sin);
-enum GemmEpilogue { kEpiStore = 0, kEpiResidual = 1, kEpiSwiglu = 2, kEpiQkvRope = 3 };
+enum GemmEpilogue { kEpiStore = 0, kEpiResidual = 1, kEpiSwiglu = 2, kEpiQkvRope = 3, kEpiPartial = 4 };
 // C[M,N] = A[M,K] W[N,K]^T; kEpiResidual adds residual[M,N]; kEpiSwiglu: W is [2N,K] (gate|up),
 // C[M,N] = silu(gate) * up.
 pvf_status launch_gemm(pvf_ctx *ctx, hipStream_t s, int dtype, GemmEpilogue epi, const void *A,

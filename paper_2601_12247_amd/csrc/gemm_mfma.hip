@@ -83,13 +83,20 @@ struct RopeArgs {
   int32_t T, H;
 };
 
+// kEpiPartial: the launch is split along K (blockIdx.y = split); every split stores its tile of float32
+// partial sums to partial[split][M][N], which splitk_finalize_kernel adds up and finishes.
+struct SplitK {
+  float *partial;
+  int32_t nk_per;                                    // k stages per split
+};
+
 template <int EPI, int BM, int BN, int BK, int kStages, int WM, int WN>
 __global__ void __launch_bounds__(64 * WM * WN)
 __attribute__((amdgpu_waves_per_eu(waves_per_simd(kStages * (BM + BN) * BK * 2, WM * WN),
                                    waves_per_simd(kStages * (BM + BN) * BK * 2, WM * WN))))
 gemm_bf16_mfma_kernel(const bf16_t *__restrict__ A, const bf16_t *__restrict__ W,
                       bf16_t *__restrict__ C, const bf16_t *__restrict__ Res, int M, int N_out,
-                      int K, int tiles_m, int tiles_n, int group_m, RopeArgs ra) {
+                      int K, int tiles_m, int tiles_n, int group_m, RopeArgs ra, SplitK sk) {
   constexpr int kThreads = 64 * WM * WN;
   constexpr int MT = BM / (32 * WM);                       // 32-row passes of the epilogue
   constexpr int MT16 = BM / (16 * WM), NT16 = BN / (16 * WN);   // 16x16 MFMA tiles per wave in each direction
@@ -141,6 +148,10 @@ gemm_bf16_mfma_kernel(const bf16_t *__restrict__ A, const bf16_t *__restrict__ W
   for (int i = 0; i < LW; ++i)
     w_off[i] = ((uint32_t)w_row<EPI, BN, WN>(i * RPI + ld_row, tile_n, N_out) * (uint32_t)K + ld_chunk * 8) * 2u;
   const char *Ab = reinterpret_cast<const char *>(A), *Wb = reinterpret_cast<const char *>(W);
+  if (EPI == kEpiPartial) {                                  // this split's range of k
+    Ab += (size_t)blockIdx.y * sk.nk_per * (BK * 2);
+    Wb += (size_t)blockIdx.y * sk.nk_per * (BK * 2);
+  }
   constexpr int kLoadsPerStage = LA + LW;
   auto issue_one = [&](int kt, int i) {                      // load i (A loads first, then W) of stage kt
     unsigned char *dst = lds + (kt % kStages) * kStage + wave * 1024;
@@ -168,7 +179,7 @@ gemm_bf16_mfma_kernel(const bf16_t *__restrict__ A, const bf16_t *__restrict__ W
 #pragma unroll
       for (int e = 0; e < 4; ++e) acc[nt][mt][e] = 0.f;
 
-  const int nk = K / BK;
+  const int nk = EPI == kEpiPartial ? sk.nk_per : K / BK;
 #pragma unroll
   for (int s = 0; s < kAhead; ++s)
     if (s < nk) {
@@ -275,7 +286,8 @@ gemm_bf16_mfma_kernel(const bf16_t *__restrict__ A, const bf16_t *__restrict__ W
   // residual epilogue, which stages float32 so that acc + residual is rounded once.
   constexpr int WTM = BM / WM, WTN = BN / WN;
   constexpr int OC = (EPI == kEpiSwiglu) ? WTN / 2 : WTN;            // output columns of this wave
-  constexpr int kElem = (EPI == kEpiResidual) ? 4 : 2;
+  constexpr bool kStageF32 = EPI == kEpiResidual || EPI == kEpiPartial;
+  constexpr int kElem = kStageF32 ? 4 : 2;
   constexpr int kStride = OC * kElem + 16;                           // padded row of the staging area
   constexpr int LPR = OC / 8;                                        // lanes per output row (8 columns each)
   constexpr int kRowsPerInstr = 64 / LPR;
@@ -333,7 +345,7 @@ gemm_bf16_mfma_kernel(const bf16_t *__restrict__ A, const bf16_t *__restrict__ W
 #pragma unroll
         for (int nt = 0; nt < NT16; ++nt) {
           const int col = nt * 16 + 4 * fq;
-          if (EPI == kEpiResidual)
+          if (kStageF32)
             *reinterpret_cast<float4 *>(wrow + col * 4) = make_float4(acc[nt][m16][0], acc[nt][m16][1], acc[nt][m16][2], acc[nt][m16][3]);
           else
             *reinterpret_cast<uint2 *>(wrow + col * 2) = make_uint2(pack_bf16x2(acc[nt][m16][0], acc[nt][m16][1]),
@@ -412,6 +424,14 @@ gemm_bf16_mfma_kernel(const bf16_t *__restrict__ A, const bf16_t *__restrict__ W
       const int r = j * kRowsPerInstr + rd_row;
       const int m = m0 + wm * WTM + mt * 32 + r;
       const int64_t o = (int64_t)m * N_out + out_col0 + rd_col;
+      if (EPI == kEpiPartial) {
+        if (m < M) {
+          float4 *dst = reinterpret_cast<float4 *>(sk.partial + (int64_t)blockIdx.y * M * N_out + o);
+          dst[0] = *reinterpret_cast<const float4 *>(my + r * kStride + rd_col * 4);
+          dst[1] = *reinterpret_cast<const float4 *>(my + r * kStride + rd_col * 4 + 16);
+        }
+        continue;
+      }
       uint4 out;
       if (EPI == kEpiResidual) {
         const float4 x0 = *reinterpret_cast<const float4 *>(my + r * kStride + rd_col * 4);
@@ -431,7 +451,7 @@ gemm_bf16_mfma_kernel(const bf16_t *__restrict__ A, const bf16_t *__restrict__ W
 
 template <int EPI, int BM, int BN, int BK, int ST, int WM, int WN>
 pvf_status run(pvf_ctx *ctx, hipStream_t s, const void *A, const void *W, void *C, const void *Res,
-               int M, int N_out, int K, const RopeArgs &ra) {
+               int M, int N_out, int K, const RopeArgs &ra, const SplitK &sk = SplitK{nullptr, 0}, int splits = 1) {
   constexpr int kLdsBytes = ST * (BM + BN) * BK * 2;
   static_assert(kLdsBytes <= 160 * 1024, "LDS ring exceeds the 160 KB of a CU");
   static bool configured = false;
@@ -450,8 +470,8 @@ pvf_status run(pvf_ctx *ctx, hipStream_t s, const void *A, const void *W, void *
   constexpr int kBand = BM > BN ? 4 : 8;
   const int n_bands = (tiles_m + kBand - 1) / kBand;
   const int group_m = (tiles_m + n_bands - 1) / n_bands;
-  gemm_bf16_mfma_kernel<EPI, BM, BN, BK, ST, WM, WN><<<grid, 64 * WM * WN, kLdsBytes, s>>>(
-      (const bf16_t *)A, (const bf16_t *)W, (bf16_t *)C, (const bf16_t *)Res, M, N_out, K, tiles_m, tiles_n, group_m, ra);
+  gemm_bf16_mfma_kernel<EPI, BM, BN, BK, ST, WM, WN><<<dim3(grid, splits), 64 * WM * WN, kLdsBytes, s>>>(
+      (const bf16_t *)A, (const bf16_t *)W, (bf16_t *)C, (const bf16_t *)Res, M, N_out, K, tiles_m, tiles_n, group_m, ra, sk);
   PVF_LAUNCH_CHECK(ctx, "gemm_mfma");
   return PVF_OK;
 }
@@ -519,9 +539,105 @@ int pick_config(GemmEpilogue epi, int M, int N, int K) {
   return best;
 }
 
+// Adds the partial sums of a split-K launch in split order (deterministic) and finishes like the
+// fused epilogues: store, + residual (rounded once), or SwiGLU of the gate | up halves of a partial row.
+// One thread = 8 consecutive output columns of one row.  Nw = length of a partial row.
+template <int EPI>
+__global__ void __launch_bounds__(256)
+splitk_finalize_kernel(const float *__restrict__ partial, int splits, int M, int Nw, int N_out,
+                       bf16_t *__restrict__ out, const bf16_t *__restrict__ res) {
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const int per_row = N_out / 8;
+  if (idx >= (int64_t)M * per_row) return;
+  const int m = (int)(idx / per_row), c = (int)(idx % per_row) * 8;
+  float v[8], u[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) v[e] = u[e] = 0.f;
+  for (int z = 0; z < splits; ++z) {
+    const float *row = partial + ((int64_t)z * M + m) * Nw + c;
+    const float4 a0 = *reinterpret_cast<const float4 *>(row), a1 = *reinterpret_cast<const float4 *>(row + 4);
+    v[0] += a0.x; v[1] += a0.y; v[2] += a0.z; v[3] += a0.w; v[4] += a1.x; v[5] += a1.y; v[6] += a1.z; v[7] += a1.w;
+    if (EPI == kEpiSwiglu) {
+      const float4 b0 = *reinterpret_cast<const float4 *>(row + N_out), b1 = *reinterpret_cast<const float4 *>(row + N_out + 4);
+      u[0] += b0.x; u[1] += b0.y; u[2] += b0.z; u[3] += b0.w; u[4] += b1.x; u[5] += b1.y; u[6] += b1.z; u[7] += b1.w;
+    }
+  }
+  if (EPI == kEpiSwiglu) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) v[e] = silu_f(v[e]) * u[e];
+  }
+  const int64_t o = (int64_t)m * N_out + c;
+  if (EPI == kEpiResidual) {
+    const uint4 rs = *reinterpret_cast<const uint4 *>(res + o);
+    const uint32_t rw[4] = {rs.x, rs.y, rs.z, rs.w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      v[2 * e] += __uint_as_float(rw[e] << 16);
+      v[2 * e + 1] += __uint_as_float(rw[e] & 0xffff0000u);
+    }
+  }
+  *reinterpret_cast<uint4 *>(out + o) = make_uint4(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]),
+                                                   pack_bf16x2(v[4], v[5]), pack_bf16x2(v[6], v[7]));
+}
+
+constexpr int kSplitMaxRows = 384;   // launches with more rows have enough tiles without splitting K
+
+// Tile height and number of splits of a split-K launch; splits = 0: not possible.  The estimate is rounds of
+// workgroups over the chip x (k stages per workgroup + ~8 stages' worth of prologue and epilogue).
+void splitk_plan(int M, int Nw, int K, size_t ws_floats, int *tile, int *splits) {
+  *tile = M <= 64 ? 7 : M <= 192 ? 8 : 5;                    // 64x128, 192x128, 320x128: all rows in one or two row tiles
+  const int bm = M <= 64 ? 64 : M <= 192 ? 192 : 320;
+  const int slots = M <= 64 ? 512 : 256;                     // the 4-wave shape runs two workgroups per CU
+  const int tiles = ((M + bm - 1) / bm) * (Nw / 128), nk = K / 64;
+  *splits = 0;
+  int best = 0;
+  for (int sp = 1; sp <= 8; sp <<= 1) {
+    if (nk % sp != 0 || nk / sp < 8 || (size_t)sp * M * Nw > ws_floats) continue;
+    // 64-row tiles do little arithmetic per stage and are bound by the bytes in flight: as many workgroups as fit twice
+    const int cost = M <= 64 ? (tiles * sp <= 2 * slots ? -sp : 1) : ((tiles * sp + slots - 1) / slots) * (nk / sp + 8);
+    if (*splits == 0 || cost < best) { *splits = sp; best = cost; }
+  }
+}
+
 }  // namespace
 
 bool gemm_mfma_supported(int dtype, GemmEpilogue epi, int M, int N, int K);
+
+// Few rows (window forward of the K/V-cached rounds): tiles as tall as the launch, so that every
+// weight row goes from L2 to a CU once, and K split over 2-8 workgroups per tile to fill the chip and
+// to shorten the serial k loop; a second small kernel adds the partial sums.  ws: float32 scratch.
+bool gemm_mfma_splitk_supported(int dtype, GemmEpilogue epi, int M, int N, int K, size_t ws_floats) {
+  if (epi == kEpiQkvRope || epi == kEpiPartial || !gemm_mfma_supported(dtype, epi, M, N, K)) return false;
+  const int Nw = epi == kEpiSwiglu ? 2 * N : N;
+  if (M > kSplitMaxRows || Nw % 128 != 0 || N % 8 != 0 || Nw > 32768) return false;
+  int tile, splits;
+  splitk_plan(M, Nw, K, ws_floats, &tile, &splits);
+  // one split only for SwiGLU, whose fused epilogue the tall tiles (wave tiles 32 columns wide) do not have
+  return splits >= 2 || (splits == 1 && epi == kEpiSwiglu && M > 128);
+}
+
+pvf_status launch_gemm_mfma_splitk(pvf_ctx *ctx, hipStream_t s, GemmEpilogue epi, const void *A, const void *W,
+                                   void *C, const void *residual, int M, int N, int K, float *ws, size_t ws_floats) {
+  const uintptr_t al = (uintptr_t)A | (uintptr_t)W | (uintptr_t)C | (uintptr_t)residual | (uintptr_t)ws;
+  PVF_REQUIRE(ctx, (al & 15u) == 0, PVF_EINVAL, "gemm_mfma: operands must be 16-byte aligned");
+  const int Nw = epi == kEpiSwiglu ? 2 * N : N;
+  int tile, splits;
+  splitk_plan(M, Nw, K, ws_floats, &tile, &splits);
+  PVF_REQUIRE(ctx, splits >= 1 && ws != nullptr, PVF_ESHAPE, "gemm_mfma: no split-K plan for M=%d N=%d K=%d", M, N, K);
+  const SplitK sk{ws, K / 64 / splits};
+  pvf_status st;
+  if (tile == 7) st = run<kEpiPartial, 64, 128, 64, 3, 2, 2>(ctx, s, A, W, nullptr, nullptr, M, Nw, K, RopeArgs{}, sk, splits);
+  else if (tile == 8) st = run<kEpiPartial, 192, 128, 64, 3, 2, 4>(ctx, s, A, W, nullptr, nullptr, M, Nw, K, RopeArgs{}, sk, splits);
+  else st = run<kEpiPartial, 320, 128, 64, 2, 2, 4>(ctx, s, A, W, nullptr, nullptr, M, Nw, K, RopeArgs{}, sk, splits);
+  if (st != PVF_OK) return st;
+  const int blocks = (int)(((int64_t)M * (N / 8) + 255) / 256);
+  if (epi == kEpiSwiglu) splitk_finalize_kernel<kEpiSwiglu><<<blocks, 256, 0, s>>>(ws, splits, M, Nw, N, (bf16_t *)C, nullptr);
+  else if (epi == kEpiResidual) splitk_finalize_kernel<kEpiResidual><<<blocks, 256, 0, s>>>(ws, splits, M, Nw, N, (bf16_t *)C, (const bf16_t *)residual);
+  else splitk_finalize_kernel<kEpiStore><<<blocks, 256, 0, s>>>(ws, splits, M, Nw, N, (bf16_t *)C, nullptr);
+  PVF_LAUNCH_CHECK(ctx, "splitk_finalize");
+  return PVF_OK;
+}
+
 
 // QKV projection with the rotary embedding and the key-contiguous copy of v fused into the
 // epilogue (see RopeArgs).  qkv [M, 3*H*128], vt [M/T, H, 128, T], cos_sin [T, 64].
@@ -560,6 +676,7 @@ pvf_status launch_gemm_mfma(pvf_ctx *ctx, hipStream_t s, GemmEpilogue epi, const
     case kEpiResidual: return run_cfg<kEpiResidual>(ctx, s, cfg, A, W, C, residual, M, N, K);
     case kEpiSwiglu: return run_cfg<kEpiSwiglu>(ctx, s, cfg, A, W, C, residual, M, N, K);
     case kEpiQkvRope: break;                     // has its own entry (launch_gemm_mfma_qkv_rope)
+    case kEpiPartial: break;                     // launch_gemm_mfma_splitk
   }
   return PVF_EINVAL;
 }

@@ -19,6 +19,8 @@ struct pvf_ctx {
   // workspace (device)
   void *h = nullptr, *xn = nullptr, *qkv = nullptr, *att = nullptr, *act = nullptr, *vt = nullptr;
   void *hrows = nullptr, *logits = nullptr;
+  float *splitk_ws = nullptr;          // float32 partial sums of the split-K GEMMs (bf16 contexts)
+  size_t splitk_floats = 0;
   int32_t *seq_slot = nullptr, *row_pos = nullptr;
   float2 *cos_sin = nullptr;           // [max_T, d_head/2]
   int32_t *status_host = nullptr;      // pinned, 2*G words per round
@@ -81,6 +83,9 @@ pvf_status launch_attention_simple(pvf_ctx *, hipStream_t, int, const void *, vo
 bool gemm_mfma_supported(int dtype, GemmEpilogue epi, int M, int N, int K);
 pvf_status launch_gemm_mfma(pvf_ctx *, hipStream_t, GemmEpilogue, const void *, const void *, void *,
                             const void *, int, int, int);
+bool gemm_mfma_splitk_supported(int dtype, GemmEpilogue epi, int M, int N, int K, size_t ws_floats);
+pvf_status launch_gemm_mfma_splitk(pvf_ctx *, hipStream_t, GemmEpilogue, const void *, const void *, void *, const void *,
+                                   int, int, int, float *, size_t);
 bool gemm_mfma_qkv_rope_supported(int dtype, int M, int N, int K, int T, int H);
 pvf_status launch_gemm_mfma_qkv_rope(pvf_ctx *, hipStream_t, const void *, const void *, void *, void *, const float2 *,
                                      int, int, int, int, int);
@@ -99,6 +104,8 @@ static bool force_simple() {
 
 pvf_status launch_gemm(pvf_ctx *ctx, hipStream_t s, int dtype, GemmEpilogue epi, const void *A,
                        const void *W, void *C, const void *residual, int M, int N, int K) {
+  if (!force_simple() && ctx && ctx->splitk_ws && gemm_mfma_splitk_supported(dtype, epi, M, N, K, ctx->splitk_floats))
+    return launch_gemm_mfma_splitk(ctx, s, epi, A, W, C, residual, M, N, K, ctx->splitk_ws, ctx->splitk_floats);
   if (!force_simple() && gemm_mfma_supported(dtype, epi, M, N, K))
     return launch_gemm_mfma(ctx, s, epi, A, W, C, residual, M, N, K);
   return launch_gemm_simple(ctx, s, dtype, epi, A, W, C, residual, M, N, K);
@@ -168,7 +175,7 @@ static void free_ws(pvf_ctx *c) {
   for (hipEvent_t e : c->ev_pool) (void)hipEventDestroy(e);
   c->ev_pool.clear();
   void *ptrs[] = {c->h, c->xn, c->qkv, c->att, c->act, c->vt, c->hrows, c->logits, c->seq_slot, c->row_pos, c->cos_sin,
-                  c->kcache, c->vcache};
+                  c->kcache, c->vcache, c->splitk_ws};
   for (void *p : ptrs) if (p) (void)hipFree(p);
   if (c->status_host) (void)hipHostFree(c->status_host);
   if (c->seq_host) (void)hipHostFree(c->seq_host);
@@ -218,7 +225,9 @@ extern "C" pvf_status pvf_create(pvf_ctx **out, const pvf_model_cfg *m, const pv
       {&c->act, M * ff * (int64_t)c->esize},    {&c->hrows, rows * d * (int64_t)c->esize},
       {&c->logits, rows * (int64_t)m->vocab * (int64_t)c->esize},
       {(void **)&c->seq_slot, (int64_t)max_seqs * 4}, {(void **)&c->row_pos, rows * 4},
-      {(void **)&c->cos_sin, (int64_t)max_T * half * 8}};
+      {(void **)&c->cos_sin, (int64_t)max_T * half * 8},
+      // partial sums of the few-row GEMMs: up to 384 rows x (splits x row length) of at most 49152 floats
+      {(void **)&c->splitk_ws, m->dtype == PVF_BF16 ? (int64_t)384 * 49152 * 4 : 16}};
   for (auto &r : req) {
     hipError_t e = hipMalloc(r.p, (size_t)r.bytes);
     if (e != hipSuccess) {
@@ -229,6 +238,8 @@ extern "C" pvf_status pvf_create(pvf_ctx **out, const pvf_model_cfg *m, const pv
     }
     c->ws_bytes += r.bytes;
   }
+  c->splitk_floats = m->dtype == PVF_BF16 ? (size_t)384 * 49152 : 0;
+  if (m->dtype != PVF_BF16) { (void)hipFree(c->splitk_ws); c->splitk_ws = nullptr; }
   // rotary table in double precision on the host: angle = pos * theta^(-2i/d_head)
   {
     std::vector<float2> tab((size_t)max_T * half);

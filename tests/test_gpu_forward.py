@@ -162,6 +162,24 @@ def test_forward_bf16_two_layer_small_within_5e2():
         assert np.abs(got[s] - want).max() <= 5e-2
 
 
+@pytest.mark.parametrize("S_,T", [(1, 256), (2, 160), (1, 64)])
+def test_forward_bf16_few_rows_split_k_within_5e2(S_, T):
+    """Forwards of at most 384 token rows take the split-K GEMMs (tall tiles, K divided over several
+    workgroups, float32 partial sums added by a second kernel) for the O, gate/up and down projections."""
+    shape = S.ModelShape(n_layers=2, d_model=1024, n_heads=8, d_ff=2048, vocab=2048, mask_id=2047, rope_theta=5e5)
+    w = S.make_weights(shape, seed=5, round_to_bf16=True)
+    ctx = make_context(shape, to_device(w, torch.bfloat16), max_seqs=S_, max_T=T, max_rows=64)
+    toks = np.stack([S.make_prompt(10 + s, T, shape.vocab, shape.mask_id) for s in range(S_)])
+    toks[:, T - 40:] = shape.mask_id
+    rows = np.tile(np.arange(T - 64, T, dtype=np.int32), (S_, 1))
+    got = ctx.forward(dev(toks, torch.int32), dev(rows, torch.int32)).float().cpu().numpy()
+    again = ctx.forward(dev(toks, torch.int32), dev(rows, torch.int32)).float().cpu().numpy()
+    assert np.array_equal(got, again)                       # partial sums are added in a fixed order
+    for s in range(S_):
+        want = O.forward(toks[s], w, oracle_model_cfg(shape), rows=rows[s])
+        assert np.abs(got[s] - want).max() <= 5e-2
+
+
 def test_forward_shape_errors():
     shape = S.TINY
     ctx = make_context(shape, to_device(S.make_weights(shape, seed=0)), max_seqs=1, max_T=32, max_rows=8)
