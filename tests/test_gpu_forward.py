@@ -146,6 +146,24 @@ def test_forward_is_batch_invariant_and_deterministic():
     assert torch.equal(one[0], a[2])       # a canvas's logits do not depend on its batch mates
 
 
+def test_forward_bf16_mfma_is_batch_invariant_above_384_rows():
+    """On the MFMA path every GEMM tile shape accumulates k in the same order, attention works per
+    canvas: with more than 384 token rows per launch (below that the GEMMs split K, which changes the
+    rounding order with the launch size) a canvas's bf16 logits are bit-identical whatever rides along."""
+    shape = S.ModelShape(n_layers=2, d_model=256, n_heads=2, d_ff=512, vocab=2048, mask_id=2047, rope_theta=5e5)
+    w = to_device(S.make_weights(shape, seed=4, round_to_bf16=True), torch.bfloat16)
+    ctx = make_context(shape, w, max_seqs=4, max_T=512, max_rows=64)
+    toks = np.stack([S.make_prompt(20 + s, 512, shape.vocab, shape.mask_id) for s in range(4)])
+    rows = np.tile(np.arange(448, 512, dtype=np.int32), (4, 1))
+    four = ctx.forward(dev(toks, torch.int32), dev(rows, torch.int32))
+    again = ctx.forward(dev(toks, torch.int32), dev(rows, torch.int32))
+    assert torch.equal(four, again)
+    for sub in ([1], [0, 3], [2, 1, 0]):
+        part = ctx.forward(dev(toks[sub], torch.int32), dev(rows[sub], torch.int32))
+        for i, sq in enumerate(sub):
+            assert torch.equal(part[i], four[sq]), f"canvas {sq} in a batch of {len(sub)}"
+
+
 def test_forward_bf16_two_layer_small_within_5e2():
     """bf16 storage path on a reduced-width model (plain kernels or MFMA, whichever the
     dispatcher picks for these shapes)."""

@@ -1,6 +1,6 @@
 """Every tile shape of the bf16 MFMA GEMM accumulates the k index of an output element in the same
-order with the same instruction, so all shapes must give bit-identical results (the forward's
-batch invariance rests on this: the shape is chosen from M).  Each shape is forced through the
+order with the same instruction, so all shapes must give bit-identical results (the batch invariance
+of forwards above 384 token rows rests on this: the shape is chosen from M).  Each shape is forced through the
 PVF_GEMM_TILE environment variable, which the library reads once per process, hence subprocesses."""
 import hashlib
 import os
