@@ -227,8 +227,9 @@ extern "C" pvf_status pvf_create(pvf_ctx **out, const pvf_model_cfg *m, const pv
       {(void **)&c->seq_slot, (int64_t)max_seqs * 4}, {(void **)&c->row_pos, rows * 4},
       {(void **)&c->cos_sin, (int64_t)max_T * half * 8},
       // partial sums of the few-row GEMMs: up to 384 rows x (splits x row length) of at most 49152 floats
-      {(void **)&c->splitk_ws, m->dtype == PVF_BF16 ? (int64_t)384 * 49152 * 4 : 16}};
+      {(void **)&c->splitk_ws, m->dtype == PVF_BF16 ? (int64_t)384 * 49152 * 4 : 0}};
   for (auto &r : req) {
+    if (r.bytes == 0) continue;
     hipError_t e = hipMalloc(r.p, (size_t)r.bytes);
     if (e != hipSuccess) {
       set_error(nullptr, "pvf_create: hipMalloc(%lld bytes) failed: %s", (long long)r.bytes, hipGetErrorString(e));
@@ -238,8 +239,7 @@ extern "C" pvf_status pvf_create(pvf_ctx **out, const pvf_model_cfg *m, const pv
     }
     c->ws_bytes += r.bytes;
   }
-  c->splitk_floats = m->dtype == PVF_BF16 ? (size_t)384 * 49152 : 0;
-  if (m->dtype != PVF_BF16) { (void)hipFree(c->splitk_ws); c->splitk_ws = nullptr; }
+  c->splitk_floats = c->splitk_ws ? (size_t)384 * 49152 : 0;
   // rotary table in double precision on the host: angle = pos * theta^(-2i/d_head)
   {
     std::vector<float2> tab((size_t)max_T * half);
