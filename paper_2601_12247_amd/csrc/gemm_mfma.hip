@@ -218,10 +218,11 @@ gemm_bf16_mfma_kernel(const bf16_t *__restrict__ A, const bf16_t *__restrict__ W
   // A steady stage (one that still prefetches) has compile-time wait counts and no branches.
   constexpr int kMfmaPerStep = MT16 * NT16;
   constexpr int kVmPerStep = KS > 1 ? (kLoadsPerStage + KS - 2) / (KS - 1) : kLoadsPerStage;
+  constexpr int kLateStride = (MT16 * NT16 - 4) / (LA + LW) >= 2 ? 2 : 1;   // every second MFMA where the k-step is long enough
   constexpr int kBarrierAt = MT16 - 1 < 4 ? MT16 - 1 : 4;   // MFMAs of the last k-step issued before the barrier
   // the A reads are spread over MFMAs (kBarrierAt, kReadEnd): up to the start of the last pass
   constexpr int kReadEnd = (NT16 - 1) * MT16 > kBarrierAt + 2 ? (NT16 - 1) * MT16 : kBarrierAt + 2;
-  static_assert(!kLate || kLoadsPerStage <= kMfmaPerStep - kBarrierAt, "one refill load per MFMA after the barrier");
+  static_assert(!kLate || kLoadsPerStage * kLateStride <= kMfmaPerStep - kBarrierAt + kLateStride - 1, "the refill loads fit into the last k-step");
   static_assert(kReadEnd <= kMfmaPerStep, "the A reads fit into the k-step");
   wait_stages(min(kAhead - 1, nk - 1));
   __builtin_amdgcn_s_barrier();
@@ -267,8 +268,10 @@ gemm_bf16_mfma_kernel(const bf16_t *__restrict__ A, const bf16_t *__restrict__ W
             if ((q * kMfmaPerStep) / kVmPerStep == i && kk * kVmPerStep + q < kLoadsPerStage)
               issue_one(kt + kStages - 1, kk * kVmPerStep + q);
         }
-        if (kLate && kSteady && last && i >= kBarrierAt && i - kBarrierAt < kLoadsPerStage)
-          issue_one(kt + kStages, i - kBarrierAt);           // slot kt % kStages was freed by the barrier above
+        // slot kt % kStages was freed by the barrier above: one refill load after every kLateStride-th MFMA
+        if (kLate && kSteady && last && i >= kBarrierAt && (i - kBarrierAt) % kLateStride == 0 &&
+            (i - kBarrierAt) / kLateStride < kLoadsPerStage)
+          issue_one(kt + kStages, (i - kBarrierAt) / kLateStride);
         __builtin_amdgcn_sched_barrier(0);
       }
     }
