@@ -154,8 +154,12 @@ attention_mfma_kernel(const bf16_t *__restrict__ qkv, const bf16_t *__restrict__
 #pragma unroll
       for (int e = 0; e < 16; ++e) mx = fmaxf(mx, s[t][e]);
     mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-    const float m_new = fmaxf(m_run, mx);
-    const float alpha = fast_exp2((m_run - m_new) * c);      // first tile: exp2(-inf) = 0
+    // The running maximum moves only when the tile's maximum exceeds it by more than 8 in the exponent
+    // (p then stays below 2^8, no overflow anywhere): the accumulators are rescaled in the first
+    // tiles and almost never afterwards, instead of whenever one of the 32 queries sees a new maximum.
+    const bool upd = (mx - m_run) * c > 8.0f;                // first tile: m_run = -inf
+    const float m_new = upd ? mx : m_run;
+    const float alpha = upd ? fast_exp2((m_run - m_new) * c) : 1.0f;   // first tile: exp2(-inf) = 0
     const float nmc = -m_new * c;
     bf16x8 pf[4];                                            // "B" operand of the 4 key k-steps
 #pragma unroll
