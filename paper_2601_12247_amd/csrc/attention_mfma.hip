@@ -16,6 +16,8 @@
 //     double-buffered.
 #include "common.h"
 
+#include <type_traits>
+
 namespace pvf {
 namespace {
 
@@ -126,13 +128,22 @@ attention_mfma_kernel(const bf16_t *__restrict__ qkv, const bf16_t *__restrict__
   for (int e = 0; e < 8; ++e) ones[e] = (bf16_t)(fr == 0 ? 1.0f : 0.0f);
   const float c = kLog2e / sqrtf((float)DH);
 
+  // per-lane LDS offsets of the operand reads; the buffer, the key sub-tile and the d tile are
+  // compile-time offsets on top (the loop below is unrolled over the two buffers)
+  int k_rd[8], v_rd[4];
+#pragma unroll
+  for (int ks = 0; ks < 8; ++ks) k_rd[ks] = fr * 256 + (((ks * 2 + fh) ^ (fr & 15)) << 4);
+#pragma unroll
+  for (int ks2 = 0; ks2 < 4; ++ks2) v_rd[ks2] = fr * 128 + (((2 * ks2 + fh) ^ ((fr >> 1) & 7)) << 4);
+
   const int nk = T / TK;
   issue_loads(0, 0);
-  for (int kt = 0; kt < nk; ++kt) {
+  auto tile = [&](int kt, auto buf_c) {
+    constexpr int kBuf = decltype(buf_c)::value;
     __builtin_amdgcn_s_waitcnt(0x0f70);          // vmcnt(0)
     __syncthreads();
-    if (kt + 1 < nk) issue_loads(kt + 1, (kt + 1) & 1);
-    const unsigned char *ks_ = lds + (kt & 1) * kStage;
+    if (kt + 1 < nk) issue_loads(kt + 1, kBuf ^ 1);
+    const unsigned char *ks_ = lds + kBuf * kStage;
     const unsigned char *vs_ = ks_ + kKTile;
 
     // ---- S^T = K Q^T : 2 key sub-tiles x 8 k-steps ----
@@ -141,8 +152,7 @@ attention_mfma_kernel(const bf16_t *__restrict__ qkv, const bf16_t *__restrict__
     for (int ks = 0; ks < 8; ++ks) {
 #pragma unroll
       for (int t = 0; t < 2; ++t) {
-        const int key = t * 32 + fr;
-        const bf16x8 kf = *reinterpret_cast<const bf16x8 *>(ks_ + key * 256 + (((ks * 2 + fh) ^ (key & 15)) << 4));
+        const bf16x8 kf = *reinterpret_cast<const bf16x8 *>(ks_ + t * 32 * 256 + k_rd[ks]);   // key t*32 + fr
         // the first k-step starts from a constant zero accumulator: no registers to clear per tile
         s[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], ks == 0 ? kZero16 : s[t], 0, 0, 0);
       }
@@ -184,16 +194,19 @@ attention_mfma_kernel(const bf16_t *__restrict__ qkv, const bf16_t *__restrict__
     for (int ks2 = 0; ks2 < 4; ++ks2) {
 #pragma unroll
       for (int t = 0; t < 4; ++t) {
-        const int vr = t * 32 + fr;
-        const int swz = (vr >> 1) & 7;
-        // vt stores each group of 16 keys as {0-3, 8-11 | 4-7, 12-15}: chunk 2*ks2 + fh is this lane's 8 keys
-        const bf16x8 vf = *reinterpret_cast<const bf16x8 *>(vs_ + vr * 128 + (((2 * ks2 + fh) ^ swz) << 4));
+        // d row t*32 + fr; vt stores each group of 16 keys as {0-3, 8-11 | 4-7, 12-15}: chunk 2*ks2 + fh is this lane's 8 keys
+        const bf16x8 vf = *reinterpret_cast<const bf16x8 *>(vs_ + t * 32 * 128 + v_rd[ks2]);
         o[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[ks2], o[t], 0, 0, 0);
       }
       // row sums of P on the matrix pipe (a "V^T" row of ones): the vector ALU is the busier unit here
       ol = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ones, pf[ks2], ol, 0, 0, 0);
     }
+  };
+  for (int kt = 0; kt + 1 < nk; kt += 2) {
+    tile(kt, std::integral_constant<int, 0>{});
+    tile(kt + 1, std::integral_constant<int, 1>{});
   }
+  if (nk & 1) tile(nk - 1, std::integral_constant<int, 0>{});
   const float l_run = __shfl(ol[0], fr, 64);                 // row 0 of that product: lane q % 32, register 0
 
   // ---- out[q][head*128 + d]: lane holds 4 consecutive d per accumulator group ----
