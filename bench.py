@@ -35,14 +35,14 @@ LOGIT_SCALE = 12.0             # calibrated once: K=0 decoding of this model lan
 # HBM-side bytes per launch (L2 fills + write-backs) from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE passes over
 # this script, scaled by what the counters read for a plain 256 MiB copy; the passes and the arithmetic are in
 # profiles/bench_c3_llada8b_pmc_hbm_traffic.txt
-TRAFFIC_GEMM = 479.3e6         # mean over the GEMM launches of the timed mix (algorithmic: 187.2e6)
+TRAFFIC_GEMM = 411.4e6         # mean over the GEMM launches of the timed mix (algorithmic: 182.0e6)
 TRAFFIC_STAGE1 = 518.5e6       # [2048, 126464] bf16 logits (algorithmic: 518.0e6)
 
 
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=60)
+    ap.add_argument("--steps", type=int, default=240)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-epilogue", action="store_true")
@@ -57,20 +57,22 @@ def parse():
     return ap.parse_args()
 
 
-def timed_rounds(ctx, B, cfg, prompt, bitmap, steps, warmup, torch):
-    """Runs warmup + steps rounds of a continuing decode (restarting when the canvas is complete)."""
+def timed_rounds(ctx, B, cfg, prompts, bitmap, steps, warmup, torch):
+    """Runs warmup + steps rounds of a continuing decode; a finished canvas is followed by the next prompt
+    of the list (a random model's trajectory, hence its tokens per round, varies a lot from prompt to prompt)."""
     st = B.State(1, cfg)
-    ctx.state_init(st, prompt)
-    n_seq = 1
+    ctx.state_init(st, prompts[0])
+    n_seq, which = 1, 0
 
     def one_round():
-        nonlocal n_seq
+        nonlocal n_seq, which
         ctx.round(st, bitmap, n_seq)
         nd, dn, nc = st.n_drafts.cpu(), st.done.cpu(), st.n_commit.cpu()      # per-round status read-back
         committed = int(nc.sum())
         used = n_seq
         if int(dn[0]):
-            ctx.state_init(st, prompt)
+            which = (which + 1) % len(prompts)
+            ctx.state_init(st, prompts[which])
             n_seq = 1
         else:
             n_seq = 1 + int(nd[0])
@@ -189,24 +191,34 @@ def main():
     T, R = P + Gn, 2 * bl
     weights = W.random_model(dims, seed=0)
     ctx = W.make_context(dims, weights, max_seqs=1 + K, max_T=T, max_rows=R)
-    prompt = W.random_prompts(1, P, dims["vocab"], dims["mask_id"], seed=1)
+    prompts = [W.random_prompts(1, P, dims["vocab"], dims["mask_id"], seed=1 + i) for i in range(8)]
+    n_dec = 4                                               # whole decodes per setting for the TPF / NFE figures
     bitmap = W.random_plan_bitmap(512, dims["vocab"], dims["mask_id"], seed=2)
     cfg = B.DecodeCfg(block_len=bl, prompt_len=P, gen_len=Gn, K=K, tau_high=0.9, logit_scale=LOGIT_SCALE)
     torch.cuda.synchronize()
 
-    dt, tokens, seqs, prof = timed_rounds(ctx, B, cfg, prompt, bitmap, a.steps, a.warmup, torch)
+    dt, tokens, seqs, prof = timed_rounds(ctx, B, cfg, prompts, bitmap, a.steps, a.warmup, torch)
     g = prof["gemm"]
     gemm_tflops = g["flops"] / (g["ms"] * 1e-3) / 1e12 if g["ms"] else 0.0
     tpf = tokens / a.steps
     flops_total = W.flops_per_round(dims, 1, T, R) * seqs          # per canvas x canvases forwarded
 
-    # whole decodes for TPF / NFE, PVF and K = 0
+    # whole decodes of the first n_dec prompts for TPF / NFE, PVF and K = 0
+    def decode_all(c, warm=False):
+        tot = {"rounds": 0, "ms": 0.0, "seqs": 0, "base": 0, "plan": 0, "ar": 0}
+        for pr in prompts[:n_dec]:
+            if warm:
+                ctx.decode(B.State(1, c), pr, bitmap)                       # cache allocation, tile shapes
+            out, st_ = ctx.decode(B.State(1, c), pr, bitmap)
+            assert int((out == dims["mask_id"]).sum()) == 0
+            tot["rounds"] += st_.rounds; tot["ms"] += st_.ms_total; tot["seqs"] += st_.seq_forwards
+            tot["base"] += st_.n_base; tot["plan"] += st_.n_plan; tot["ar"] += st_.n_ar
+        return tot
+
     s_pvf = s_thr = None
     if not a.no_decodes:
-        out, s_pvf = ctx.decode(B.State(1, cfg), prompt, bitmap)
-        cfg0 = B.DecodeCfg(block_len=bl, prompt_len=P, gen_len=Gn, K=0, tau_high=0.9, logit_scale=LOGIT_SCALE)
-        out0, s_thr = ctx.decode(B.State(1, cfg0), prompt, bitmap)
-        assert int((out == dims["mask_id"]).sum()) == 0 and int((out0 == dims["mask_id"]).sum()) == 0
+        s_pvf = decode_all(cfg)
+        s_thr = decode_all(B.DecodeCfg(block_len=bl, prompt_len=P, gen_len=Gn, K=0, tau_high=0.9, logit_scale=LOGIT_SCALE))
 
     res = {
         "metric": "committed_tokens_per_s", "value": round(tokens / dt, 2), "unit": "tokens/s",
@@ -232,25 +244,23 @@ def main():
                          "one NVIDIA H200, trained weights, KV cache; not comparable with random-init weights",
     }
     if s_pvf is not None:
+        gen = n_dec * Gn
         res.update({
-        "pvf_decode": {"nfe": s_pvf.rounds, "tokens_per_forward": round(Gn / s_pvf.rounds, 3),
-                       "tokens_per_s": round(Gn / s_pvf.ms_total * 1e3, 2), "canvases_forwarded": s_pvf.seq_forwards,
-                       "committed_by_threshold": s_pvf.n_base, "by_planning": s_pvf.n_plan, "by_ar": s_pvf.n_ar},
-        "threshold_decoding": {"nfe": s_thr.rounds, "tokens_per_forward": round(Gn / s_thr.rounds, 3),
-                               "tokens_per_s": round(Gn / s_thr.ms_total * 1e3, 2)}})
-        res["pvf_vs_threshold"] = {"tpf_ratio": round(s_thr.rounds / s_pvf.rounds, 3),
+        "pvf_decode": {"prompts": n_dec, "nfe": s_pvf["rounds"], "tokens_per_forward": round(gen / s_pvf["rounds"], 3),
+                       "tokens_per_s": round(gen / s_pvf["ms"] * 1e3, 2), "canvases_forwarded": s_pvf["seqs"],
+                       "committed_by_threshold": s_pvf["base"], "by_planning": s_pvf["plan"], "by_ar": s_pvf["ar"]},
+        "threshold_decoding": {"prompts": n_dec, "nfe": s_thr["rounds"], "tokens_per_forward": round(gen / s_thr["rounds"], 3),
+                               "tokens_per_s": round(gen / s_thr["ms"] * 1e3, 2)}})
+        res["pvf_vs_threshold"] = {"tpf_ratio": round(s_thr["rounds"] / s_pvf["rounds"], 3),
                                    "tokens_per_s_ratio": round(res["pvf_decode"]["tokens_per_s"] /
                                                                res["threshold_decoding"]["tokens_per_s"], 3)}
-    if s_pvf is not None:
-        # the same two decodes with the block-level K/V cache (the setting of the paper's tokens/s; approximate)
+        # the same decodes with the block-level K/V cache (the setting of the paper's tokens/s; approximate)
         kv = {}
         for name, k in (("pvf", K), ("threshold", 0)):
             c = B.DecodeCfg(block_len=bl, prompt_len=P, gen_len=Gn, K=k, tau_high=0.9, logit_scale=LOGIT_SCALE, kv_cache=1)
-            ctx.decode(B.State(1, c), prompt, bitmap)                       # warm-up (cache allocation, tile shapes)
-            o, s_kv = ctx.decode(B.State(1, c), prompt, bitmap)
-            assert int((o == dims["mask_id"]).sum()) == 0
-            kv[name] = {"nfe": s_kv.rounds, "tokens_per_s": round(Gn / s_kv.ms_total * 1e3, 2),
-                        "ms_per_round": round(s_kv.ms_total / s_kv.rounds, 3), "canvases_forwarded": s_kv.seq_forwards}
+            s_kv = decode_all(c, warm=(name == "pvf"))
+            kv[name] = {"prompts": n_dec, "nfe": s_kv["rounds"], "tokens_per_s": round(gen / s_kv["ms"] * 1e3, 2),
+                        "ms_per_round": round(s_kv["ms"] / s_kv["rounds"], 3), "canvases_forwarded": s_kv["seqs"]}
         res["kv_cache_decode"] = kv
     if not a.no_decodes:
         res["forward_full_batch"] = {"c3_5x512": forward_full_batch(ctx, W, dims, 1 + K, T, R, torch, 10)}
