@@ -5,8 +5,9 @@ A "step" is one PVF round: one batched forward over the backbone canvas and its 
 followed by the decision epilogue (stage 1 over the window logits, stage 2 verify / commit /
 propose).  The default workload is the LLaDA-8B-shaped bf16 random-init model, batch 1,
 256 prompt + 256 masked tokens, block 32, tau_high 0.9, K = 4, planning vocabulary 512 ids
-(third entry of the benchmark's configs).  Weights and prompt are generated on the device
-before the timed region, so every input is resident in HBM when timing starts.
+(third entry of the benchmark's configs).  Weights and prompts are generated on the device
+before the timed region, so every input is resident in HBM when timing starts; the timed rounds
+decode eight seeded prompts one after the other (a finished canvas is followed by the next prompt).
 
 Prints ONE JSON line.  `value` = tokens committed during the timed rounds / wall time.
 Extra objects:
