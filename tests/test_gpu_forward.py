@@ -115,6 +115,22 @@ def test_qkv_attention_fused_epilogue_equals_separate_passes(S_, T, H):
     assert (out.float() - ref_out.float()).abs().max().item() <= 2e-2 * scale
 
 
+@pytest.mark.parametrize("dtype,S_,T,H,dh", [(torch.float32, 2, 48, 2, 64), (torch.bfloat16, 1, 100, 2, 128),
+                                             (torch.bfloat16, 2, 64, 3, 32)])
+def test_qkv_attention_without_the_fused_epilogue(dtype, S_, T, H, dh):
+    """Shapes the fused rotary epilogue does not cover (float32, head sizes other than 128, canvas
+    lengths that are no multiple of 64): pvf_qkv_attention is pvf_gemm + pvf_rope_attention."""
+    d = H * dh
+    g = torch.Generator(device="cuda").manual_seed(S_ * T + dh)
+    x = torch.randn(S_ * T, d, device="cuda", generator=g).to(dtype)
+    w = (torch.randn(3 * d, d, device="cuda", generator=g) * (1.2 / d ** 0.5)).to(dtype)
+    qkv, out = B.qkv_attention(x, w, S_, T, H, dh, 1e4)
+    ref_qkv = B.gemm(x, w)
+    ref_out = B.rope_attention(ref_qkv, S_, T, H, dh, 1e4)
+    torch.cuda.synchronize()
+    assert torch.equal(qkv, ref_qkv) and torch.equal(out, ref_out)
+
+
 def test_forward_tiny_fp32_logits_within_1e4():
     shape = S.TINY
     w = S.make_weights(shape, seed=0)
@@ -180,7 +196,7 @@ def test_forward_bf16_two_layer_small_within_5e2():
         assert np.abs(got[s] - want).max() <= 5e-2
 
 
-@pytest.mark.parametrize("S_,T", [(1, 256), (2, 160), (1, 64)])
+@pytest.mark.parametrize("S_,T", [(1, 256), (2, 160), (1, 64), (3, 128), (2, 96)])
 def test_forward_bf16_few_rows_split_k_within_5e2(S_, T):
     """Forwards of at most 384 token rows take the split-K GEMMs (tall tiles, K divided over several
     workgroups, float32 partial sums added by a second kernel) for the O, gate/up and down projections."""
