@@ -40,6 +40,10 @@ TRAFFIC_GEMM = 411.4e6         # mean over the GEMM launches of the timed mix (a
 TRAFFIC_STAGE1 = 518.5e6       # [2048, 126464] bf16 logits (algorithmic: 518.0e6)
 
 
+# full-batch forwards: sequences per forward, canvas length, window rows per canvas
+FULL_BATCH = {"c3_5x512": (5, 512, 64), "c4_9x1280": (9, 1280, 128), "c5_80x1024": (80, 1024, 64)}
+
+
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -52,6 +56,9 @@ def parse():
                          "without K/V cache) and the full-batch forward timing; used for profiling runs")
     ap.add_argument("--all-configs", action="store_true",
                     help="also time one full-batch forward of the 9 x 1280 and 80 x 1024 configurations")
+    ap.add_argument("--forward-only", choices=sorted(FULL_BATCH), default=None,
+                    help="time nothing but min(--steps, 20) full-batch forwards of the named configuration and print that figure "
+                         "(one JSON line); used for profiling runs of the larger configurations")
     ap.add_argument("--pmc-reference", action="store_true",
                     help="also run a plain device-to-device copy of 256 MiB (reference for scaling "
                          "rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
@@ -191,6 +198,11 @@ def main():
     K, bl, P, Gn = 4, 32, 256, 256
     T, R = P + Gn, 2 * bl
     weights = W.random_model(dims, seed=0)
+    if a.forward_only:
+        S_, T_, R_ = FULL_BATCH[a.forward_only]
+        c2 = W.make_context(dims, weights, max_seqs=S_, max_T=T_, max_rows=R_)
+        print(json.dumps({"forward_full_batch": {a.forward_only: forward_full_batch(c2, W, dims, S_, T_, R_, torch, min(a.steps, 20))}}))
+        return
     ctx = W.make_context(dims, weights, max_seqs=1 + K, max_T=T, max_rows=R)
     prompts = [W.random_prompts(1, P, dims["vocab"], dims["mask_id"], seed=1 + i) for i in range(8)]
     n_dec = 4                                               # whole decodes per setting for the TPF / NFE figures
@@ -268,7 +280,8 @@ def main():
     if a.all_configs and not a.no_decodes:
         del ctx
         torch.cuda.empty_cache()
-        for name, (S_, T_, R_) in (("c4_9x1280", (9, 1280, 128)), ("c5_80x1024", (80, 1024, 64))):
+        for name in ("c4_9x1280", "c5_80x1024"):
+            S_, T_, R_ = FULL_BATCH[name]
             c2 = W.make_context(dims, weights, max_seqs=S_, max_T=T_, max_rows=R_)
             res["forward_full_batch"][name] = forward_full_batch(c2, W, dims, S_, T_, R_, torch, 3)
             del c2

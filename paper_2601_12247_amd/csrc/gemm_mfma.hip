@@ -60,8 +60,16 @@ template <int N> __device__ __forceinline__ void wait_vmcnt() {
 //  SwiGLU:  the tile covers BN/2 output columns; inside each wave's BN/WN tile rows groups of 32
 //           rows alternate gate / up for the same 32 columns, so silu(g)*u pairs accumulators
 //           of one lane (16-row MFMA sub-tiles 4P, 4P+1 with 4P+2, 4P+3).
+//  QKV with rotary embedding (ff = 3 d): in the q and k thirds a wave's 64 tile rows are columns
+//           [32g, 32g + 32) of a head followed by their rotation partners [64 + 32g, 64 + 32g + 32)
+//           (g = wave % 2), so the pair (i, i + 64) meets in one lane (sub-tiles t and t + 2).
 template <int EPI, int BN, int WN>
 __device__ __forceinline__ int w_row(int r, int tile_n, int ff) {
+  if (EPI == kEpiQkvRope) {
+    if (tile_n * BN >= 2 * (ff / 3)) return tile_n * BN + r;           // v third: as it is
+    const int wn = r >> 6, t = (r >> 4) & 3, e = r & 15;
+    return tile_n * BN + (wn >> 1) * 128 + (t >> 1) * 64 + (wn & 1) * 32 + (t & 1) * 16 + e;
+  }
   if (EPI != kEpiSwiglu) return tile_n * BN + r;
   constexpr int WT = BN / WN;
   const int wn = r / WT, t = (r % WT) >> 5, e = r & 31;
@@ -312,28 +320,62 @@ gemm_bf16_mfma_kernel(const bf16_t *__restrict__ A, const bf16_t *__restrict__ W
       }
   }
   __syncthreads();                                                   // every wave is done with the ring
-  unsigned char *my = lds + wave * (32 * kStride);
   const int rope_third = EPI == kEpiQkvRope ? (tile_n * BN) / (N_out / 3) : 2;   // 0 = q, 1 = k, 2 = v (uniform per workgroup)
-  const int col_in_head = (out_col0 + rd_col) & 127;
+  // v third of the QKV projection: a wave keeps two passes (64 keys) in its staging area, so that the
+  // key-contiguous copy is written in whole 128-byte lines; columns are XOR-swizzled by the 16-key block
+  // of the row, which makes the transposing 2-byte reads free of bank conflicts.
+  constexpr int kVPasses = (EPI == kEpiQkvRope && WTM % 64 == 0) ? 2 : 1;
+  static_assert(WM * WN * kVPasses * 32 * kStride <= kStages * kStage, "v staging area exceeds the LDS ring");
+  const bool v_tile = EPI == kEpiQkvRope && rope_third == 2;
+  unsigned char *my = lds + wave * ((v_tile ? kVPasses : 1) * 32 * kStride);
+  // rotary epilogue: cos / sin of the lane's rows (2 halves of 16) and columns (2 sub-tiles x 4 pairs) of a
+  // pass, requested one pass ahead
+  const int rope_g = wn & 1;
+  float4 csr[EPI == kEpiQkvRope ? 2 : 1][2][2][2];
+  auto load_cs = [&](int mt) {
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+      for (int nt = 0; nt < 2; ++nt) {
+        const int m = m0 + wm * WTM + mt * 32 + h * 16 + fr;
+        const float4 *cs4 = reinterpret_cast<const float4 *>(ra.cos_sin + (int64_t)(min(m, M - 1) % ra.T) * 64 + rope_g * 32 + nt * 16 + 4 * fq);
+        csr[EPI == kEpiQkvRope ? mt & 1 : 0][h][nt][0] = cs4[0];
+        csr[EPI == kEpiQkvRope ? mt & 1 : 0][h][nt][1] = cs4[1];
+      }
+  };
+  if (EPI == kEpiQkvRope && rope_third < 2) load_cs(0);
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt) {
-    // rotary epilogue: the cos / sin of this pass's rows are requested before the staging, which hides their latency
-    float4 csr[EPI == kEpiQkvRope ? kRowIters : 1][4];
-    if (EPI == kEpiQkvRope && rope_third < 2) {
-#pragma unroll
-      for (int j = 0; j < kRowIters; ++j) {
-        const int m = m0 + wm * WTM + mt * 32 + j * kRowsPerInstr + rd_row;
-        const float4 *cs4 = reinterpret_cast<const float4 *>(ra.cos_sin + (int64_t)(min(m, M - 1) % ra.T) * 64 + (col_in_head & 63));
-#pragma unroll
-        for (int e = 0; e < 4; ++e) csr[j][e] = cs4[e];
-      }
-    }
+    if (EPI == kEpiQkvRope && rope_third < 2 && mt + 1 < MT) load_cs(mt + 1);
     // lane: row h*16 + lane%16 of the pass (h = 16-row half), 4 consecutive columns per n sub-tile
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
-      unsigned char *wrow = my + (h * 16 + fr) * kStride;
+      const int vp = v_tile ? mt % kVPasses : 0;                        // pass inside the v staging group
+      unsigned char *wrow = my + (vp * 32 + h * 16 + fr) * kStride;
+      const int xs = v_tile ? (2 * vp + h) << 3 : 0;                    // column swizzle of this 16-row block
       const int m16 = 2 * mt + h;
-      if (EPI == kEpiSwiglu) {
+      if (EPI == kEpiQkvRope && rope_third < 2) {
+        // a = column i of the head (sub-tile nt), b = column i + 64 (sub-tile nt + 2), both rounded to bf16 first
+        // (the values a separate rotary pass would read): i <- a cos - b sin, i + 64 <- b cos + a sin
+#pragma unroll
+        for (int nt = 0; nt < 2; ++nt) {
+          constexpr int kHalf = NT16 / 2;                     // 2 here; keeps the index valid in the other instances
+          const int nb = nt % kHalf + kHalf;
+          const uint32_t aw[2] = {pack_bf16x2(acc[nt % kHalf][m16][0], acc[nt % kHalf][m16][1]), pack_bf16x2(acc[nt % kHalf][m16][2], acc[nt % kHalf][m16][3])};
+          const uint32_t bw[2] = {pack_bf16x2(acc[nb][m16][0], acc[nb][m16][1]), pack_bf16x2(acc[nb][m16][2], acc[nb][m16][3])};
+          uint32_t lo[2], up[2];
+#pragma unroll
+          for (int e = 0; e < 2; ++e) {
+            const float4 c4 = csr[EPI == kEpiQkvRope ? mt & 1 : 0][h][nt][e];
+            const float a0 = __uint_as_float(aw[e] << 16), a1 = __uint_as_float(aw[e] & 0xffff0000u);
+            const float b0 = __uint_as_float(bw[e] << 16), b1 = __uint_as_float(bw[e] & 0xffff0000u);
+            lo[e] = pack_bf16x2(a0 * c4.x - b0 * c4.y, a1 * c4.z - b1 * c4.w);
+            up[e] = pack_bf16x2(b0 * c4.x + a0 * c4.y, b1 * c4.z + a1 * c4.w);
+          }
+          *reinterpret_cast<uint2 *>(wrow + (nt * 16 + 4 * fq) * 2) = make_uint2(lo[0], lo[1]);
+          *reinterpret_cast<uint2 *>(wrow + (32 + nt * 16 + 4 * fq) * 2) = make_uint2(up[0], up[1]);
+        }
+      } else if (EPI == kEpiSwiglu) {
 #pragma unroll
         for (int P = 0; P < NT16 / 4; ++P)
 #pragma unroll
@@ -347,7 +389,7 @@ gemm_bf16_mfma_kernel(const bf16_t *__restrict__ A, const bf16_t *__restrict__ W
       } else {
 #pragma unroll
         for (int nt = 0; nt < NT16; ++nt) {
-          const int col = nt * 16 + 4 * fq;
+          const int col = (nt * 16 + 4 * fq) ^ xs;
           if (kStageF32)
             *reinterpret_cast<float4 *>(wrow + col * 4) = make_float4(acc[nt][m16][0], acc[nt][m16][1], acc[nt][m16][2], acc[nt][m16][3]);
           else
@@ -357,69 +399,57 @@ gemm_bf16_mfma_kernel(const bf16_t *__restrict__ A, const bf16_t *__restrict__ W
       }
     }
     if (EPI == kEpiQkvRope) {
-      static_assert(EPI != kEpiQkvRope || ((WTN == 64 && WN % 2 == 0) || WTN == 128), "a head is one or two wave tiles wide");
+      static_assert(EPI != kEpiQkvRope || (WTN == 64 && WN % 2 == 0), "a head is two wave tiles wide");
       const int d_model = N_out / 3;
       const int m_base = m0 + wm * WTM + mt * 32;
-      if (WTN == 64) __syncthreads();                                // the partner wave's half of the head is staged
       if (rope_third < 2) {
-        const bool upper = col_in_head >= 64;
-        const unsigned char *partner = (WTN == 64) ? lds + (wave ^ 1) * (32 * kStride) + rd_col * 2
-                                                   : my + (rd_col ^ 64) * 2;
+        // staged row: 32 columns from 32g of the head, then the 32 from 64 + 32g
+        const int col = tile_n * BN + (wn >> 1) * 128 + rope_g * 32 + (rd_col < 32 ? rd_col : rd_col + 32);
 #pragma unroll
         for (int j = 0; j < 32 / kRowsPerInstr; ++j) {
           const int r = j * kRowsPerInstr + rd_row;
           const int m = m_base + r;
-          const uint4 own = *reinterpret_cast<const uint4 *>(my + r * kStride + rd_col * 2);
-          const uint4 oth = *reinterpret_cast<const uint4 *>(partner + r * kStride);
-          if (m < M) {
-            const uint32_t ow[4] = {own.x, own.y, own.z, own.w}, pw[4] = {oth.x, oth.y, oth.z, oth.w};
-            uint32_t res[4];
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-              const float4 c4 = csr[EPI == kEpiQkvRope ? j : 0][e];
-              const float2 c0 = make_float2(c4.x, c4.y), c1 = make_float2(c4.z, c4.w);
-              const float a0 = __uint_as_float(ow[e] << 16), a1 = __uint_as_float(ow[e] & 0xffff0000u);
-              const float b0 = __uint_as_float(pw[e] << 16), b1 = __uint_as_float(pw[e] & 0xffff0000u);
-              // lower half: x*cos - partner*sin; upper half: x*cos + partner*sin
-              const float r0 = upper ? a0 * c0.x + b0 * c0.y : a0 * c0.x - b0 * c0.y;
-              const float r1 = upper ? a1 * c1.x + b1 * c1.y : a1 * c1.x - b1 * c1.y;
-              res[e] = pack_bf16x2(r0, r1);
-            }
-            *reinterpret_cast<uint4 *>(C + (int64_t)m * N_out + out_col0 + rd_col) = make_uint4(res[0], res[1], res[2], res[3]);
-          }
+          if (m < M) *reinterpret_cast<uint4 *>(C + (int64_t)m * N_out + col) =
+                         *reinterpret_cast<const uint4 *>(my + r * kStride + rd_col * 2);
         }
       } else {
+        const int vp = mt % kVPasses;
 #pragma unroll
         for (int j = 0; j < 32 / kRowsPerInstr; ++j) {               // v as it is ...
           const int r = j * kRowsPerInstr + rd_row;
+          const int rl = vp * 32 + r;                                // row inside the staging group
           const int m = m_base + r;
           if (m < M) *reinterpret_cast<uint4 *>(C + (int64_t)m * N_out + out_col0 + rd_col) =
-                         *reinterpret_cast<const uint4 *>(my + r * kStride + rd_col * 2);
+                         *reinterpret_cast<const uint4 *>(my + rl * kStride + ((rd_col ^ ((rl >> 4) << 3)) * 2));
         }
-        if (m_base < M) {                                            // ... and key-contiguous: lane = one d column, 32 keys
-          const int seq = m_base / ra.T, t0 = m_base % ra.T;
+        // ... and key-contiguous, once the group's passes are staged: a lane gathers the 8 keys of one 16-byte
+        // chunk of one d column (each 16 keys are stored as {0-3, 8-11 | 4-7, 12-15}); the lanes of a store
+        // cover all chunks of 64 / chunks neighbouring columns
+        const int key0 = m_base - vp * 32;
+        if ((vp == kVPasses - 1 || mt == MT - 1) && key0 < M) {
+          const int chunks = 4 * (vp + 1);                           // 16-byte chunks per column: 4 or 8
+          const int seq = key0 / ra.T, t0 = key0 % ra.T;
           const int vcol0 = out_col0 - 2 * d_model;                  // column inside the v third
+          const int g = lane % chunks, blk = g >> 1;
+          const unsigned char *src = my + (16 * blk + 4 * (g & 1)) * kStride;
 #pragma unroll
-          for (int cc = 0; cc < WTN / 64; ++cc) {
-            const int c = cc * 64 + lane;
-            uint32_t w[16];
+          for (int it = 0; it < chunks; ++it) {
+            const int c = it * (64 / chunks) + lane / chunks;
+            const unsigned char *sc = src + ((c ^ (blk << 3)) * 2);
+            uint32_t w[4];
 #pragma unroll
-            for (int r2 = 0; r2 < 16; ++r2) {
-              const uint32_t lo = *reinterpret_cast<const uint16_t *>(my + (2 * r2) * kStride + c * 2);
-              const uint32_t hi = *reinterpret_cast<const uint16_t *>(my + (2 * r2 + 1) * kStride + c * 2);
-              w[r2] = lo | (hi << 16);
+            for (int e = 0; e < 4; ++e) {                            // key pairs (0,1) (2,3) (8,9) (10,11) of the chunk's half
+              const int kr = (e & 1) * 2 + (e >> 1) * 8;
+              const uint32_t lo = *reinterpret_cast<const uint16_t *>(sc + kr * kStride);
+              const uint32_t hi = *reinterpret_cast<const uint16_t *>(sc + (kr + 1) * kStride);
+              w[e] = lo | (hi << 16);
             }
             const int head = (vcol0 + c) >> 7, dcol = (vcol0 + c) & 127;
-            uint4 *dst = reinterpret_cast<uint4 *>(ra.vt + (((int64_t)seq * ra.H + head) * 128 + dcol) * ra.T + t0);
-#pragma unroll
-            for (int g = 0; g < 2; ++g) {                             // each 16 keys stored as {0-3, 8-11 | 4-7, 12-15}
-              dst[2 * g] = make_uint4(w[8 * g], w[8 * g + 1], w[8 * g + 4], w[8 * g + 5]);
-              dst[2 * g + 1] = make_uint4(w[8 * g + 2], w[8 * g + 3], w[8 * g + 6], w[8 * g + 7]);
-            }
+            *reinterpret_cast<uint4 *>(ra.vt + (((int64_t)seq * ra.H + head) * 128 + dcol) * ra.T + t0 + g * 8) =
+                make_uint4(w[0], w[1], w[2], w[3]);
           }
         }
       }
-      if (WTN == 64) __syncthreads();                                // before the next 32 rows overwrite the staging area
       continue;
     }
 #pragma unroll
