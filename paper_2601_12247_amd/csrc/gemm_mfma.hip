@@ -89,6 +89,7 @@ struct RopeArgs {
   const float2 *cos_sin;
   bf16_t *vt;
   int32_t T, H;
+  int32_t store_v;                                   // 0: the v third of C is not written (only vt)
 };
 
 // kEpiPartial: the launch is split along K (blockIdx.y = split); every split stores its tile of float32
@@ -414,6 +415,7 @@ gemm_bf16_mfma_kernel(const bf16_t *__restrict__ A, const bf16_t *__restrict__ W
         }
       } else {
         const int vp = mt % kVPasses;
+        if (ra.store_v)
 #pragma unroll
         for (int j = 0; j < 32 / kRowsPerInstr; ++j) {               // v as it is ...
           const int r = j * kRowsPerInstr + rd_row;
@@ -681,13 +683,13 @@ bool gemm_mfma_qkv_rope_supported(int dtype, int M, int N, int K, int T, int H) 
 }
 
 pvf_status launch_gemm_mfma_qkv_rope(pvf_ctx *ctx, hipStream_t s, const void *A, const void *W, void *qkv,
-                                     void *vt, const float2 *cos_sin, int M, int N, int K, int T, int H) {
+                                     void *vt, const float2 *cos_sin, int M, int N, int K, int T, int H, bool store_v) {
   const uintptr_t al = (uintptr_t)A | (uintptr_t)W | (uintptr_t)qkv | (uintptr_t)vt;
   PVF_REQUIRE(ctx, (al & 15u) == 0, PVF_EINVAL, "gemm_mfma: operands must be 16-byte aligned");
   const int cfg = pick_config(kEpiQkvRope, M, N, K);
   PVF_REQUIRE(ctx, cfg >= 0, PVF_ESHAPE, "gemm_mfma: no tile shape with a rotary epilogue for N=%d", N);
   RopeArgs ra;
-  ra.cos_sin = cos_sin; ra.vt = (bf16_t *)vt; ra.T = T; ra.H = H;
+  ra.cos_sin = cos_sin; ra.vt = (bf16_t *)vt; ra.T = T; ra.H = H; ra.store_v = store_v;
   return run_cfg<kEpiQkvRope>(ctx, s, cfg, A, W, qkv, nullptr, M, N, K, ra);
 }
 

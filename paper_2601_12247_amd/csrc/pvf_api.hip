@@ -88,7 +88,7 @@ pvf_status launch_gemm_mfma_splitk(pvf_ctx *, hipStream_t, GemmEpilogue, const v
                                    int, int, int, float *, size_t);
 bool gemm_mfma_qkv_rope_supported(int dtype, int M, int N, int K, int T, int H);
 pvf_status launch_gemm_mfma_qkv_rope(pvf_ctx *, hipStream_t, const void *, const void *, void *, void *, const float2 *,
-                                     int, int, int, int, int);
+                                     int, int, int, int, int, bool store_v);
 bool attention_mfma_supported(int dtype, int T, int d_head);
 pvf_status launch_attention_mfma(pvf_ctx *, hipStream_t, const void *, const void *, void *, int, int, int);
 pvf_status launch_rope_vt(pvf_ctx *, hipStream_t, void *, void *, int, int, int, const float2 *);
@@ -298,11 +298,13 @@ static pvf_status forward_impl(pvf_ctx *c, hipStream_t s, const int32_t *tokens,
   for (int l = 0; l < m.n_layers; ++l) {
     RUN(launch_rmsnorm(c, s, dt, c->h, c->attn_norm[l], c->xn, M, d, m.rms_eps));
     if (fused_rope) {
-      // the QKV projection rotates q, k and writes the key-contiguous v in its epilogue
+      // the QKV projection rotates q, k and writes the key-contiguous v in its epilogue; the row-major v third
+      // has a reader only when the K/V cache keeps its values in that layout
+      const bool store_v = capture_spg > 0 && !c->cache_vt;
       {
         ProfScope ps(c, s, PVF_PROF_GEMM, 2.0 * M * (double)(3 * d) * d,
-                     (double)c->esize * ((double)M * d + 3.0 * d * d + (double)M * 3 * d + (double)M * d));   // + the key-contiguous v
-        RUN(launch_gemm_mfma_qkv_rope(c, s, c->xn, c->wqkv[l], c->qkv, c->vt, c->cos_sin, M, 3 * d, d, T, H));
+                     (double)c->esize * ((double)M * d + 3.0 * d * d + (double)M * (store_v ? 3 : 2) * d + (double)M * d));   // q, k (, v) + the key-contiguous v
+        RUN(launch_gemm_mfma_qkv_rope(c, s, c->xn, c->wqkv[l], c->qkv, c->vt, c->cos_sin, M, 3 * d, d, T, H, store_v));
       }
       ProfScope ps(c, s, PVF_PROF_ATTENTION, 4.0 * S * (double)T * T * d, 0.0);
       RUN(launch_attention_mfma(c, s, c->qkv, c->vt, c->att, S, T, H));
@@ -764,7 +766,7 @@ extern "C" pvf_status pvf_qkv_attention(void *stream, int32_t dtype, const void 
   }
   if (st == PVF_OK) {
     if (mfma_att && gemm_mfma_qkv_rope_supported(dtype, M, 3 * d, d, T, n_heads)) {
-      st = launch_gemm_mfma_qkv_rope(nullptr, s, x, wqkv, qkv, vt, dev, M, 3 * d, d, T, n_heads);
+      st = launch_gemm_mfma_qkv_rope(nullptr, s, x, wqkv, qkv, vt, dev, M, 3 * d, d, T, n_heads, true);
       if (st == PVF_OK) st = launch_attention_mfma(nullptr, s, qkv, vt, out, S, T, n_heads);
     } else {
       st = launch_gemm(nullptr, s, dtype, kEpiStore, x, wqkv, qkv, nullptr, M, 3 * d, d);
