@@ -23,9 +23,6 @@ namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
-typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-typedef float floatx2 __attribute__((ext_vector_type(2)));
-typedef uint32_t uintx4 __attribute__((ext_vector_type(4)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef __attribute__((address_space(1))) const void gptr_t;
 typedef __attribute__((address_space(3))) void lptr_t;
@@ -52,16 +49,11 @@ struct WinArgs {
 template <bool WIN>
 __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
 attention_mfma_kernel(const bf16_t *__restrict__ qkv, const bf16_t *__restrict__ vt,
-                      bf16_t *__restrict__ out, int T, int H, int nq, int n_pairs, WinArgs wa) {
+                      bf16_t *__restrict__ out, int T, int H, WinArgs wa) {
   __shared__ __attribute__((aligned(1024))) unsigned char lds[2 * kStage];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int fr = lane & 31, fh = lane >> 5;
-  // Workgroups are dealt to the 8 XCDs round-robin by their index.  All query blocks of a (canvas, head)
-  // pair go to one XCD, one after the other, so that pair's K and V^T enter a single L2 once instead of
-  // all eight: XCD c = index % 8 takes the pairs c, c + 8, c + 16, ...
-  const int pair = ((int)blockIdx.x >> 3) / nq * 8 + ((int)blockIdx.x & 7);
-  if (pair >= n_pairs) return;
-  const int q0 = (((int)blockIdx.x >> 3) % nq) * TQ, head = pair % H, seq = pair / H;
+  const int q0 = blockIdx.x * TQ, head = blockIdx.y, seq = blockIdx.z;
   const int d = H * DH;
   const int TQrows = WIN ? wa.R : T;                       // query rows per canvas in qkv / out
   const int64_t row0 = (int64_t)seq * TQrows;
@@ -86,44 +78,38 @@ attention_mfma_kernel(const bf16_t *__restrict__ qkv, const bf16_t *__restrict__
     qf[ks] = *reinterpret_cast<const bf16x8 *>(qb + (int64_t)qrow * 3 * d + ks * 16 + fh * 8);
 
   // ---- global -> LDS addressing (see file header) ----
-  // K tile: slot s = i*256 + tid -> key s/16 = 16 i + tid/16, position s%16, chunk = position ^ (key & 15)
-  // V^T tile: slot s -> d-row s/8 = 32 i + tid/8, position s%8, chunk = position ^ ((row >> 1) & 7)
-  // so the four loads of a thread differ by a uniform stride only.
-  const int k_key0 = tid >> 4, k_col = ((tid & 15) ^ (k_key0 & 15)) * 8;
-  const int v_row0 = tid >> 3, v_key = ((tid & 7) ^ ((tid >> 4) & 7)) * 8;
-  const uint32_t k_off = ((uint32_t)k_key0 * 3u * (uint32_t)d + (uint32_t)k_col) * 2u;   // bytes from the tile's first key
-  const uint32_t v_off = ((uint32_t)v_row0 * (uint32_t)T + (uint32_t)v_key) * 2u;        // bytes from the tile's first key of d-row 0
-  // LDS: two K buffers, then two V^T buffers.  K and V^T of a tile are consumed in different iterations.
-  unsigned char *const kbase = lds, *const vbase = lds + 2 * kKTile;
-  auto issue_k = [&](int kt, int buf) {
-    unsigned char *dst = kbase + buf * kKTile + wave * 1024;
+  // K tile: slot s = i*256 + tid -> key s/16, position s%16, chunk = position ^ (key & 15)
+  // V^T tile: slot s -> d-row s/8, position s%8, chunk = position ^ ((row >> 1) & 7)
+  const bf16_t *k_src[4], *v_src[4];
+  int k_key[4], k_col[4], v_row[4], v_key[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int s = i * 256 + tid;
+    const int key = s >> 4, kc = (s & 15) ^ (key & 15);
+    k_src[i] = kb + (int64_t)key * 3 * d + kc * 8;
+    k_key[i] = key; k_col[i] = kc * 8;
+    const int vr = s >> 3, vc = (s & 7) ^ ((vr >> 1) & 7);
+    v_src[i] = vtb + (int64_t)vr * T + vc * 8;
+    v_row[i] = vr; v_key[i] = vc * 8;
+  }
+  auto issue_loads = [&](int kt, int buf) {
+    unsigned char *dst = lds + buf * kStage + wave * 1024;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const char *ks;
+      const bf16_t *ks, *vs;
       if (WIN) {
-        const int key = kt * TK + i * 16 + k_key0;         // canvas position of this K row
-        ks = reinterpret_cast<const char *>((key >= w0 && key < w1) ? kb + (int64_t)(key - w0) * 3 * d + k_col
-                                                                    : kcb + (int64_t)key * d + k_col);
+        const int key = kt * TK + k_key[i];                // canvas position of this K row
+        ks = (key >= w0 && key < w1) ? kb + (int64_t)(key - w0) * 3 * d + k_col[i]
+                                     : kcb + (int64_t)key * d + k_col[i];
+        const int vk = kt * TK + v_key[i];                 // first of the 8 keys of this V^T chunk
+        vs = (vk >= w0 && vk < w1) ? vtb + (int64_t)v_row[i] * wa.R + (vk - w0)
+                                   : vtcb + (int64_t)v_row[i] * T + vk;
       } else {
-        ks = reinterpret_cast<const char *>(kb) + (size_t)(kt * TK + i * 16) * 3 * d * 2 + k_off;   // uniform base + lane offset
+        ks = k_src[i] + (int64_t)kt * TK * 3 * d;
+        vs = v_src[i] + kt * TK;
       }
       __builtin_amdgcn_global_load_lds((gptr_t *)ks, (lptr_t *)(dst + i * 4096), 16, 0, 0);
-    }
-  };
-  auto issue_v = [&](int kt, int buf) {
-    unsigned char *dst = vbase + buf * kVTile + wave * 1024;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const char *vs;
-      if (WIN) {
-        const int vk = kt * TK + v_key;                    // first of the 8 keys of this V^T chunk
-        const int vr = i * 32 + v_row0;
-        vs = reinterpret_cast<const char *>((vk >= w0 && vk < w1) ? vtb + (int64_t)vr * wa.R + (vk - w0)
-                                                                  : vtcb + (int64_t)vr * T + vk);
-      } else {
-        vs = reinterpret_cast<const char *>(vtb) + ((size_t)i * 32 * T + (size_t)kt * TK) * 2 + v_off;
-      }
-      __builtin_amdgcn_global_load_lds((gptr_t *)vs, (lptr_t *)(dst + i * 4096), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((gptr_t *)vs, (lptr_t *)(dst + kKTile + i * 4096), 16, 0, 0);
     }
   };
 
@@ -133,10 +119,13 @@ attention_mfma_kernel(const bf16_t *__restrict__ qkv, const bf16_t *__restrict__
 #pragma unroll
     for (int e = 0; e < 16; ++e) o[t][e] = 0.f;
   float m_run = -INFINITY;
-  float l_part = 0.f;                                        // running sum of this lane's half of P (bf16 values, as multiplied)
+  floatx16 ol;                                               // ol[0] in lanes 0..31: running sum of P for query lane
+#pragma unroll
+  for (int e = 0; e < 16; ++e) ol[e] = 0.f;
   const floatx16 kZero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-  bf16x2 ones2;
-  ones2[0] = (bf16_t)1.0f; ones2[1] = (bf16_t)1.0f;
+  bf16x8 ones;                                               // "A" operand with row 0 = 1, rows 1..31 = 0
+#pragma unroll
+  for (int e = 0; e < 8; ++e) ones[e] = (bf16_t)(fr == 0 ? 1.0f : 0.0f);
   const float c = kLog2e / sqrtf((float)DH);
 
   // per-lane LDS offsets of the operand reads; the buffer, the key sub-tile and the d tile are
@@ -147,68 +136,34 @@ attention_mfma_kernel(const bf16_t *__restrict__ qkv, const bf16_t *__restrict__
 #pragma unroll
   for (int ks2 = 0; ks2 < 4; ++ks2) v_rd[ks2] = fr * 128 + (((2 * ks2 + fh) ^ ((fr >> 1) & 7)) << 4);
 
-  // Software pipeline over the key tiles.  Iteration kt issues, in one instruction stream,
-  //   the S^T = K Q^T MFMAs of tile kt + 1   (matrix pipe),
-  //   the online softmax of tile kt           (vector ALU; its scores were computed one iteration ago),
-  //   then the O^T += V^T P^T MFMAs of tile kt,
-  // so the matrix pipe works while the wave's exponentials run.  The scores of two tiles are alive at
-  // a time (s[parity]).  The issue order is written out and pinned with sched_barrier.
-  // K(kt + 2) and V^T(kt + 1) are requested at the top of iteration kt into the buffers that iteration
-  // kt - 1 read last; one barrier per tile.
   const int nk = T / TK;
-  floatx16 s[2][2];
-  issue_k(0, 0);
-  issue_v(0, 0);
-  if (nk > 1) issue_k(1, 1);
-  __builtin_amdgcn_s_waitcnt(0x0f70);            // vmcnt(0)
-  __syncthreads();
-#pragma unroll
-  for (int ks = 0; ks < 8; ++ks)
-#pragma unroll
-    for (int t = 0; t < 2; ++t) {
-      const bf16x8 kf = *reinterpret_cast<const bf16x8 *>(kbase + t * 32 * 256 + k_rd[ks]);   // key t*32 + fr
-      s[0][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], ks == 0 ? kZero16 : s[0][t], 0, 0, 0);
-    }
-
-  auto iter = [&](int kt, auto par_c, auto more_c) {
-    constexpr int P = decltype(par_c)::value;                // kt & 1
-    constexpr bool kMore = decltype(more_c)::value;          // a tile kt + 1 exists
-    __builtin_amdgcn_s_waitcnt(0x0f70);          // vmcnt(0): my loads of K(kt+1), V^T(kt) have landed
+  issue_loads(0, 0);
+  auto tile = [&](int kt, auto buf_c) {
+    constexpr int kBuf = decltype(buf_c)::value;
+    __builtin_amdgcn_s_waitcnt(0x0f70);          // vmcnt(0)
     __syncthreads();
-    if (kMore) {
-      if (kt + 2 < nk) issue_k(kt + 2, P);
-      issue_v(kt + 1, P ^ 1);
-    }
-    const unsigned char *kn = kbase + (P ^ 1) * kKTile;      // K(kt + 1)
-    const unsigned char *vc = vbase + P * kVTile;            // V^T(kt)
-    auto rdk = [&](int ks, int t) { return *reinterpret_cast<const bf16x8 *>(kn + t * 32 * 256 + k_rd[ks]); };
-    auto rdv = [&](int i) { return *reinterpret_cast<const bf16x8 *>(vc + (i & 3) * 32 * 128 + v_rd[i >> 2]); };
-    // S^T MFMA pair of k-step ks for tile kt + 1; afterwards its fragment registers take k-step ks + 2
-    bf16x8 kf[2][2];
-    auto s_step = [&](int ks) {
-      if (kMore) {
-#pragma unroll
-        for (int t = 0; t < 2; ++t)
-          s[P ^ 1][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks & 1][t], qf[ks], ks == 0 ? kZero16 : s[P ^ 1][t], 0, 0, 0);
-        if (ks + 2 < 8) { kf[ks & 1][0] = rdk(ks + 2, 0); kf[ks & 1][1] = rdk(ks + 2, 1); }
-      }
-    };
-    if (kMore) { kf[0][0] = rdk(0, 0); kf[0][1] = rdk(0, 1); kf[1][0] = rdk(1, 0); kf[1][1] = rdk(1, 1); }
+    if (kt + 1 < nk) issue_loads(kt + 1, kBuf ^ 1);
+    const unsigned char *ks_ = lds + kBuf * kStage;
+    const unsigned char *vs_ = ks_ + kKTile;
 
-    // ---- online softmax of tile kt for this lane's query, the S^T MFMAs of tile kt + 1 in between ----
-    float mx = s[P][0][0];
+    // ---- S^T = K Q^T : 2 key sub-tiles x 8 k-steps ----
+    floatx16 s[2];
 #pragma unroll
-    for (int e = 1; e < 16; ++e) mx = fmaxf(mx, s[P][0][e]);
-    __builtin_amdgcn_sched_barrier(0);
-    s_step(0);
-    __builtin_amdgcn_sched_barrier(0);
+    for (int ks = 0; ks < 8; ++ks) {
 #pragma unroll
-    for (int e = 0; e < 16; ++e) mx = fmaxf(mx, s[P][1][e]);
-    const float mx_other = __shfl_xor(mx, 32, 64);
-    __builtin_amdgcn_sched_barrier(0);
-    s_step(1);
-    __builtin_amdgcn_sched_barrier(0);
-    mx = fmaxf(mx, mx_other);
+      for (int t = 0; t < 2; ++t) {
+        const bf16x8 kf = *reinterpret_cast<const bf16x8 *>(ks_ + t * 32 * 256 + k_rd[ks]);   // key t*32 + fr
+        // the first k-step starts from a constant zero accumulator: no registers to clear per tile
+        s[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], ks == 0 ? kZero16 : s[t], 0, 0, 0);
+      }
+    }
+    // ---- online softmax for this lane's query ----
+    float mx = s[0][0];
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) mx = fmaxf(mx, s[t][e]);
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
     // The running maximum moves only when the tile's maximum exceeds it by more than 8 in the exponent
     // (p then stays below 2^8, no overflow anywhere): the accumulators are rescaled in the first
     // tiles and almost never afterwards, instead of whenever one of the 32 queries sees a new maximum.
@@ -216,70 +171,43 @@ attention_mfma_kernel(const bf16_t *__restrict__ qkv, const bf16_t *__restrict__
     const float m_new = upd ? mx : m_run;
     const float alpha = upd ? fast_exp2((m_run - m_new) * c) : 1.0f;   // first tile: exp2(-inf) = 0
     const float nmc = -m_new * c;
+    bf16x8 pf[4];                                            // "B" operand of the 4 key k-steps
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int u = 0; u < 2; ++u)                            // k-step u of sub-tile t: register groups 2u, 2u+1
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          pf[2 * t + u][e] = (bf16_t)fast_exp2(fmaf(s[t][8 * u + e], c, nmc));
+        }
     m_run = m_new;
-    l_part *= alpha;                                         // before this tile's probabilities are added
-    uintx4 pw[4];                                            // "B" operand of the 4 key k-steps, as packed bf16 pairs
-    // element pair p: scores 2p, 2p + 1 in the order (sub-tile t, k-step u, slot e)
-    auto p_pair = [&](int p) {
-      const int t = p >> 3, u = (p >> 2) & 1, e = (p & 3) * 2;
-      floatx2 pe;
-      pe[0] = fast_exp2(fmaf(s[P][t][8 * u + e], c, nmc));
-      pe[1] = fast_exp2(fmaf(s[P][t][8 * u + e + 1], c, nmc));
-      const bf16x2 pr = __builtin_convertvector(pe, bf16x2);
-      pw[2 * t + u][p & 3] = __builtin_bit_cast(uint32_t, pr);
-      l_part = __builtin_amdgcn_fdot2_f32_bf16(pr, ones2, l_part, false);   // row sum of what the P V product multiplies
-    };
-    bf16x8 vf[2][4];                                         // V^T fragments of a key k-step, read one k-step ahead
-#pragma unroll
-    for (int ks = 2; ks < 8; ++ks) {                         // 6 k-steps, 16 element pairs: 4, 4, 2, 2, 2, 2
-      __builtin_amdgcn_sched_barrier(0);
-      s_step(ks);
-      __builtin_amdgcn_sched_barrier(0);
-      const int first = ks < 4 ? (ks - 2) * 4 : 8 + (ks - 4) * 2, n = ks < 4 ? 4 : 2;
-#pragma unroll
-      for (int p = 0; p < n; ++p) p_pair(first + p);
-      if (ks == 6) { vf[0][0] = rdv(0); vf[0][1] = rdv(1); vf[0][2] = rdv(2); vf[0][3] = rdv(3); }
-    }
-    __builtin_amdgcn_sched_barrier(0);
     if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
 #pragma unroll
       for (int t = 0; t < 4; ++t)
 #pragma unroll
         for (int e = 0; e < 16; ++e) o[t][e] *= alpha;
+      ol[0] *= alpha;
     }
-    // ---- O^T += V^T P^T : 4 key k-steps x 4 d tiles.  k slot (fh, e) of k-step ks2 is key
-    //      16*ks2 + 4*fh + e (e < 4) or 16*ks2 + 8 + 4*fh + (e - 4): the order P came out in;
-    //      vt stores each group of 16 keys as {0-3, 8-11 | 4-7, 12-15}: chunk 2*ks2 + fh is this lane's 8 keys ----
+    // ---- O^T += V^T P^T : 4 d tiles x 4 key k-steps.  k slot (fh, e) of k-step ks2 is key
+    //      16*ks2 + 4*fh + e (e < 4) or 16*ks2 + 8 + 4*fh + (e - 4): the order P came out in ----
 #pragma unroll
     for (int ks2 = 0; ks2 < 4; ++ks2) {
-      if (ks2 + 1 < 4) {
 #pragma unroll
-        for (int t = 0; t < 4; ++t) vf[(ks2 + 1) & 1][t] = rdv((ks2 + 1) * 4 + t);
+      for (int t = 0; t < 4; ++t) {
+        // d row t*32 + fr; vt stores each group of 16 keys as {0-3, 8-11 | 4-7, 12-15}: chunk 2*ks2 + fh is this lane's 8 keys
+        const bf16x8 vf = *reinterpret_cast<const bf16x8 *>(vs_ + t * 32 * 128 + v_rd[ks2]);
+        o[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[ks2], o[t], 0, 0, 0);
       }
-      __builtin_amdgcn_sched_barrier(0);                     // the reads stay ahead of this k-step's MFMAs
-      const bf16x8 pf = __builtin_bit_cast(bf16x8, pw[ks2]);
-#pragma unroll
-      for (int t = 0; t < 4; ++t)                            // d row t*32 + fr
-        o[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[ks2 & 1][t], pf, o[t], 0, 0, 0);
-      __builtin_amdgcn_sched_barrier(0);
+      // row sums of P on the matrix pipe (a "V^T" row of ones): the vector ALU is the busier unit here
+      ol = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ones, pf[ks2], ol, 0, 0, 0);
     }
   };
-  {
-    using T0 = std::integral_constant<int, 0>;
-    using T1 = std::integral_constant<int, 1>;
-    int kt = 0;
-    for (; kt + 2 < nk; kt += 2) {
-      iter(kt, T0{}, std::true_type{});
-      iter(kt + 1, T1{}, std::true_type{});
-    }
-    if (nk - kt == 2) {
-      iter(kt, T0{}, std::true_type{});
-      iter(kt + 1, T1{}, std::false_type{});
-    } else {
-      iter(kt, T0{}, std::false_type{});
-    }
+  for (int kt = 0; kt + 1 < nk; kt += 2) {
+    tile(kt, std::integral_constant<int, 0>{});
+    tile(kt + 1, std::integral_constant<int, 1>{});
   }
-  const float l_run = l_part + __shfl_xor(l_part, 32, 64);    // the other half of the keys is in lane ^ 32
+  if (nk & 1) tile(nk - 1, std::integral_constant<int, 0>{});
+  const float l_run = __shfl(ol[0], fr, 64);                 // row 0 of that product: lane q % 32, register 0
 
   // ---- out[q][head*128 + d]: lane holds 4 consecutive d per accumulator group ----
   const int q = q0 + wave * 32 + fr;
@@ -398,8 +326,8 @@ pvf_status launch_attention_window_mfma(pvf_ctx *ctx, hipStream_t s, const void 
   wa.kc = (const bf16_t *)kc; wa.vtc = (const bf16_t *)vtc; wa.group_stride = group_stride;
   wa.seq_slot = seq_slot; wa.k_active = k_active; wa.slots_per_group = slots_per_group;
   wa.prompt_len = prompt_len; wa.block_len = block_len; wa.R = R;
-  const int nq = (R + TQ - 1) / TQ, n_pairs = n_heads * S;
-  attention_mfma_kernel<true><<<8 * ((n_pairs + 7) / 8) * nq, 256, 0, s>>>((const bf16_t *)qkv_w, (const bf16_t *)vt_w, (bf16_t *)out, T, n_heads, nq, n_pairs, wa);
+  const dim3 grid((R + TQ - 1) / TQ, n_heads, S);
+  attention_mfma_kernel<true><<<grid, 256, 0, s>>>((const bf16_t *)qkv_w, (const bf16_t *)vt_w, (bf16_t *)out, T, n_heads, wa);
   PVF_LAUNCH_CHECK(ctx, "attention_window_mfma");
   return PVF_OK;
 }
@@ -412,8 +340,8 @@ bool attention_mfma_supported(int dtype, int T, int d_head) {
 pvf_status launch_attention_mfma(pvf_ctx *ctx, hipStream_t s, const void *qkv, const void *vt,
                                  void *out, int S, int T, int n_heads) {
   if (S == 0) return PVF_OK;
-  const int nq = (T + TQ - 1) / TQ, n_pairs = n_heads * S;
-  attention_mfma_kernel<false><<<8 * ((n_pairs + 7) / 8) * nq, 256, 0, s>>>((const bf16_t *)qkv, (const bf16_t *)vt, (bf16_t *)out, T, n_heads, nq, n_pairs, WinArgs{});
+  const dim3 grid((T + TQ - 1) / TQ, n_heads, S);
+  attention_mfma_kernel<false><<<grid, 256, 0, s>>>((const bf16_t *)qkv, (const bf16_t *)vt, (bf16_t *)out, T, n_heads, WinArgs{});
   PVF_LAUNCH_CHECK(ctx, "attention_mfma");
   return PVF_OK;
 }
