@@ -107,7 +107,7 @@ gemm_bf16_mfma_kernel(const bf16_t *__restrict__ A, const bf16_t *__restrict__ W
                       bf16_t *__restrict__ C, const bf16_t *__restrict__ Res, int M, int N_out,
                       int K, int tiles_m, int tiles_n, int group_m, RopeArgs ra, SplitK sk) {
   constexpr int kThreads = 64 * WM * WN;
-  constexpr int MT = BM / (32 * WM);                       // 32-row passes of the epilogue
+  constexpr int MT = (BM / WM + 31) / 32;                  // 32-row passes of the epilogue (the last one may have 16 rows)
   constexpr int MT16 = BM / (16 * WM), NT16 = BN / (16 * WN);   // 16x16 MFMA tiles per wave in each direction
   constexpr int kATile = BM * BK * 2, kWTile = BN * BK * 2, kStage = kATile + kWTile;
   constexpr int CPR = BK / 8;                        // 16-byte chunks per LDS row
@@ -122,7 +122,8 @@ gemm_bf16_mfma_kernel(const bf16_t *__restrict__ A, const bf16_t *__restrict__ W
   // of the slot freed one stage ago over the first k-steps of a stage.
   constexpr bool kLate = kStages == 2;
   constexpr int kAhead = kLate ? kStages : kStages - 1;     // stages in flight after the prologue
-  static_assert(BM % RPI == 0 && BN % RPI == 0 && BK == 64 && BM % (32 * WM) == 0 && BN % (32 * WN) == 0, "tile shape");
+  static_assert(BM % RPI == 0 && BN % RPI == 0 && BK == 64 && BM % (16 * WM) == 0 && BN % (32 * WN) == 0, "tile shape");
+  static_assert((EPI != kEpiQkvRope && EPI != kEpiSwiglu) || BM % (32 * WM) == 0, "the rotary and SwiGLU epilogues take whole 32-row passes");
   static_assert(EPI != kEpiSwiglu || NT16 % 4 == 0, "SwiGLU pairs 32-column gate/up groups inside a wave");
   extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
   const int tid = threadIdx.x, lane = tid & 63;
@@ -315,6 +316,7 @@ gemm_bf16_mfma_kernel(const bf16_t *__restrict__ A, const bf16_t *__restrict__ W
     for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
       for (int j = 0; j < kRowIters; ++j) {
+        if (mt * 32 + j * kRowsPerInstr >= WTM) continue;            // beyond a last pass of 16 rows
         const int m = m0 + wm * WTM + mt * 32 + j * kRowsPerInstr + rd_row;
         rs[mt][j] = make_uint4(0, 0, 0, 0);
         if (m < M) rs[mt][j] = *reinterpret_cast<const uint4 *>(Res + (int64_t)m * N_out + out_col0 + rd_col);
@@ -351,6 +353,7 @@ gemm_bf16_mfma_kernel(const bf16_t *__restrict__ A, const bf16_t *__restrict__ W
     // lane: row h*16 + lane%16 of the pass (h = 16-row half), 4 consecutive columns per n sub-tile
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
+      if (2 * mt + h >= MT16) continue;                                 // a last pass of 16 rows
       const int vp = v_tile ? mt % kVPasses : 0;                        // pass inside the v staging group
       unsigned char *wrow = my + (vp * 32 + h * 16 + fr) * kStride;
       const int xs = v_tile ? (2 * vp + h) << 3 : 0;                    // column swizzle of this 16-row block
@@ -456,6 +459,7 @@ gemm_bf16_mfma_kernel(const bf16_t *__restrict__ A, const bf16_t *__restrict__ W
     }
 #pragma unroll
     for (int j = 0; j < 32 / kRowsPerInstr; ++j) {
+      if (mt * 32 + j * kRowsPerInstr >= WTM) continue;              // beyond a last pass of 16 rows
       const int r = j * kRowsPerInstr + rd_row;
       const int m = m0 + wm * WTM + mt * 32 + r;
       const int64_t o = (int64_t)m * N_out + out_col0 + rd_col;
@@ -514,14 +518,16 @@ pvf_status run(pvf_ctx *ctx, hipStream_t s, const void *A, const void *W, void *
 struct TileCfg { int bm, bn, bk, stages; double eff; bool plain_only; };
 constexpr int kNumCfg = 9;
 // Every shape for many rows runs 8 waves, two per SIMD (the two small ones 4 waves, two workgroups per CU):
-// a single wave cannot keep the matrix pipe busy with 16x16x32 MFMAs and the LDS reads between them.
-// plain_only: wave tiles 32 columns wide, which the SwiGLU and rotary epilogues cannot pair up.
+// with one wave per SIMD the 256 x 256 tile (wave tiles of 128 x 128, a third fewer LDS reads) measured 2-4 %
+// slower, smaller wave tiles far slower.
+// plain_only: wave tiles 32 columns wide, which the SwiGLU and rotary epilogues cannot pair up, or 80 rows high
+// (a last epilogue pass of 16 rows, which only the plain epilogues handle).
 constexpr TileCfg kCfg[kNumCfg] = {
     {256, 256, 64, 2, 1.00, false},   // the wide layers
     {128, 256, 64, 3, 0.89, false}, {256, 128, 64, 3, 0.885, false},
     {128, 128, 64, 3, 0.70, false},   // launches of a single round of tiles: the smallest area finishes first
     {192, 256, 64, 2, 0.93, false},   // fills the chip when M / 256 leaves many CUs idle
-    {320, 128, 64, 2, 0.78, true},    // 2560 rows = 8 tile rows: with N = 4096 exactly one tile per CU
+    {320, 128, 64, 2, 0.78, true},    // 2560 rows = 8 tile rows: with N = 4096 exactly one tile per CU (wave tiles 80 x 64)
     {64, 64, 64, 5, 0.0, true},       // few rows (window forward of the K/V-cached rounds): the GEMM streams the weights,
     {64, 128, 64, 3, 0.0, false},     // so many small workgroups with deep rings; chosen by pick_config for M <= 384
     {192, 128, 64, 3, 0.86, true}};   // 1536 rows = 8 tile rows: with N = 4096 one tile per CU
@@ -535,7 +541,7 @@ pvf_status run_cfg(pvf_ctx *ctx, hipStream_t s, int cfg, const void *A, const vo
     case 1: return run<EPI, 128, 256, 64, 3, 2, 4>(ctx, s, A, W, C, Res, M, N, K, ra);
     case 2: return run<EPI, 256, 128, 64, 3, 4, 2>(ctx, s, A, W, C, Res, M, N, K, ra);
     case 4: return run<EPI, 192, 256, 64, 2, 2, 4>(ctx, s, A, W, C, Res, M, N, K, ra);
-    case 5: if constexpr (kPlain) return run<EPI, 320, 128, 64, 2, 2, 4>(ctx, s, A, W, C, Res, M, N, K, ra); break;
+    case 5: if constexpr (kPlain) return run<EPI, 320, 128, 64, 2, 4, 2>(ctx, s, A, W, C, Res, M, N, K, ra); break;
     case 6: if constexpr (kPlain) return run<EPI, 64, 64, 64, 5, 2, 2>(ctx, s, A, W, C, Res, M, N, K, ra); break;
     case 7: return run<EPI, 64, 128, 64, 3, 2, 2>(ctx, s, A, W, C, Res, M, N, K, ra);
     case 8: if constexpr (kPlain) return run<EPI, 192, 128, 64, 3, 2, 4>(ctx, s, A, W, C, Res, M, N, K, ra); break;
@@ -663,7 +669,7 @@ pvf_status launch_gemm_mfma_splitk(pvf_ctx *ctx, hipStream_t s, GemmEpilogue epi
   pvf_status st;
   if (tile == 7) st = run<kEpiPartial, 64, 128, 64, 3, 2, 2>(ctx, s, A, W, nullptr, nullptr, M, Nw, K, RopeArgs{}, sk, splits);
   else if (tile == 8) st = run<kEpiPartial, 192, 128, 64, 3, 2, 4>(ctx, s, A, W, nullptr, nullptr, M, Nw, K, RopeArgs{}, sk, splits);
-  else st = run<kEpiPartial, 320, 128, 64, 2, 2, 4>(ctx, s, A, W, nullptr, nullptr, M, Nw, K, RopeArgs{}, sk, splits);
+  else st = run<kEpiPartial, 320, 128, 64, 2, 4, 2>(ctx, s, A, W, nullptr, nullptr, M, Nw, K, RopeArgs{}, sk, splits);
   if (st != PVF_OK) return st;
   const int blocks = (int)(((int64_t)M * (N / 8) + 255) / 256);
   if (epi == kEpiSwiglu) splitk_finalize_kernel<kEpiSwiglu><<<blocks, 256, 0, s>>>(ws, splits, M, Nw, N, (bf16_t *)C, nullptr);
