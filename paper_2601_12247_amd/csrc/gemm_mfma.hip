@@ -621,16 +621,20 @@ splitk_finalize_kernel(const float *__restrict__ partial, int splits, int M, int
                                                    pack_bf16x2(v[4], v[5]), pack_bf16x2(v[6], v[7]));
 }
 
-constexpr int kSplitMaxRows = 384;   // launches with more rows have enough tiles without splitting K
+constexpr int kSplitMaxRows = 640;   // launches with more rows have enough tiles without splitting K
 
-// Tile height and number of splits of a split-K launch; splits = 0: not possible.  The estimate is rounds of
+// Tile shape and number of splits of a split-K launch; splits = 0: not possible.  The estimate is rounds of
 // workgroups over the chip x (k stages per workgroup + ~8 stages' worth of prologue and epilogue).
+// Up to 384 rows the tiles are as tall as the launch (64x128, 192x128, 320x128: all rows in one or two row
+// tiles).  From there to 640 rows (one 512-token canvas) 128x128 tiles, and only where they would leave half
+// the chip idle (the O and down projections: 128 tiles).
 void splitk_plan(int M, int Nw, int K, size_t ws_floats, int *tile, int *splits) {
-  *tile = M <= 64 ? 7 : M <= 192 ? 8 : 5;                    // 64x128, 192x128, 320x128: all rows in one or two row tiles
-  const int bm = M <= 64 ? 64 : M <= 192 ? 192 : 320;
+  *tile = M <= 64 ? 7 : M <= 192 ? 8 : M <= 384 ? 5 : 3;
+  const int bm = M <= 64 ? 64 : M <= 192 ? 192 : M <= 384 ? 320 : 128;
   const int slots = M <= 64 ? 512 : 256;                     // the 4-wave shape runs two workgroups per CU
   const int tiles = ((M + bm - 1) / bm) * (Nw / 128), nk = K / 64;
   *splits = 0;
+  if (M > 384 && tiles > 128) return;
   int best = 0;
   for (int sp = 1; sp <= 8; sp <<= 1) {
     if (nk % sp != 0 || nk / sp < 8 || (size_t)sp * M * Nw > ws_floats) continue;
@@ -644,9 +648,10 @@ void splitk_plan(int M, int Nw, int K, size_t ws_floats, int *tile, int *splits)
 
 bool gemm_mfma_supported(int dtype, GemmEpilogue epi, int M, int N, int K);
 
-// Few rows (window forward of the K/V-cached rounds): tiles as tall as the launch, so that every
-// weight row goes from L2 to a CU once, and K split over 2-8 workgroups per tile to fill the chip and
-// to shorten the serial k loop; a second small kernel adds the partial sums.  ws: float32 scratch.
+// Few rows (window forward of the K/V-cached rounds, full forward of one short canvas): tiles as tall as
+// the launch up to 384 rows, so that every weight row goes from L2 to a CU once, and K split over 2-8
+// workgroups per tile to fill the chip and to shorten the serial k loop; a second small kernel adds the
+// partial sums.  ws: float32 scratch.
 bool gemm_mfma_splitk_supported(int dtype, GemmEpilogue epi, int M, int N, int K, size_t ws_floats) {
   if (epi == kEpiQkvRope || epi == kEpiPartial || !gemm_mfma_supported(dtype, epi, M, N, K)) return false;
   const int Nw = epi == kEpiSwiglu ? 2 * N : N;
@@ -654,7 +659,7 @@ bool gemm_mfma_splitk_supported(int dtype, GemmEpilogue epi, int M, int N, int K
   int tile, splits;
   splitk_plan(M, Nw, K, ws_floats, &tile, &splits);
   // one split only for SwiGLU, whose fused epilogue the tall tiles (wave tiles 32 columns wide) do not have
-  return splits >= 2 || (splits == 1 && epi == kEpiSwiglu && M > 128);
+  return splits >= 2 || (splits == 1 && epi == kEpiSwiglu && M > 128 && M <= 384);
 }
 
 pvf_status launch_gemm_mfma_splitk(pvf_ctx *ctx, hipStream_t s, GemmEpilogue epi, const void *A, const void *W,
@@ -667,7 +672,8 @@ pvf_status launch_gemm_mfma_splitk(pvf_ctx *ctx, hipStream_t s, GemmEpilogue epi
   PVF_REQUIRE(ctx, splits >= 1 && ws != nullptr, PVF_ESHAPE, "gemm_mfma: no split-K plan for M=%d N=%d K=%d", M, N, K);
   const SplitK sk{ws, K / 64 / splits};
   pvf_status st;
-  if (tile == 7) st = run<kEpiPartial, 64, 128, 64, 3, 2, 2>(ctx, s, A, W, nullptr, nullptr, M, Nw, K, RopeArgs{}, sk, splits);
+  if (tile == 3) st = run<kEpiPartial, 128, 128, 64, 3, 4, 2>(ctx, s, A, W, nullptr, nullptr, M, Nw, K, RopeArgs{}, sk, splits);
+  else if (tile == 7) st = run<kEpiPartial, 64, 128, 64, 3, 2, 2>(ctx, s, A, W, nullptr, nullptr, M, Nw, K, RopeArgs{}, sk, splits);
   else if (tile == 8) st = run<kEpiPartial, 192, 128, 64, 3, 2, 4>(ctx, s, A, W, nullptr, nullptr, M, Nw, K, RopeArgs{}, sk, splits);
   else st = run<kEpiPartial, 320, 128, 64, 2, 4, 2>(ctx, s, A, W, nullptr, nullptr, M, Nw, K, RopeArgs{}, sk, splits);
   if (st != PVF_OK) return st;

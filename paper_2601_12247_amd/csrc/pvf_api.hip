@@ -226,7 +226,8 @@ extern "C" pvf_status pvf_create(pvf_ctx **out, const pvf_model_cfg *m, const pv
       {&c->logits, rows * (int64_t)m->vocab * (int64_t)c->esize},
       {(void **)&c->seq_slot, (int64_t)max_seqs * 4}, {(void **)&c->row_pos, rows * 4},
       {(void **)&c->cos_sin, (int64_t)max_T * half * 8},
-      // partial sums of the few-row GEMMs: up to 384 rows x (splits x row length) of at most 49152 floats
+      // partial sums of the few-row GEMMs: rows x splits x row length, at most 384 x 49152 floats (up to 384 rows
+      // every layer GEMM may split, from there to 640 rows only those with rows of 4096 or less)
       {(void **)&c->splitk_ws, m->dtype == PVF_BF16 ? (int64_t)384 * 49152 * 4 : 0}};
   for (auto &r : req) {
     if (r.bytes == 0) continue;

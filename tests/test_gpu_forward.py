@@ -162,15 +162,16 @@ def test_forward_is_batch_invariant_and_deterministic():
     assert torch.equal(one[0], a[2])       # a canvas's logits do not depend on its batch mates
 
 
-def test_forward_bf16_mfma_is_batch_invariant_above_384_rows():
+def test_forward_bf16_mfma_is_batch_invariant_above_640_rows():
     """On the MFMA path every GEMM tile shape accumulates k in the same order, attention works per
-    canvas: with more than 384 token rows per launch (below that the GEMMs split K, which changes the
-    rounding order with the launch size) a canvas's bf16 logits are bit-identical whatever rides along."""
+    canvas: with more than 640 token rows per launch (up to there GEMMs may split K, which changes the
+    rounding order with the launch size) a canvas's bf16 logits are bit-identical whatever rides along.
+    (The output head has 64 rows per canvas: its K = 256 is too short to be split.)"""
     shape = S.ModelShape(n_layers=2, d_model=256, n_heads=2, d_ff=512, vocab=2048, mask_id=2047, rope_theta=5e5)
     w = to_device(S.make_weights(shape, seed=4, round_to_bf16=True), torch.bfloat16)
-    ctx = make_context(shape, w, max_seqs=4, max_T=512, max_rows=64)
-    toks = np.stack([S.make_prompt(20 + s, 512, shape.vocab, shape.mask_id) for s in range(4)])
-    rows = np.tile(np.arange(448, 512, dtype=np.int32), (4, 1))
+    ctx = make_context(shape, w, max_seqs=4, max_T=704, max_rows=64)
+    toks = np.stack([S.make_prompt(20 + s, 704, shape.vocab, shape.mask_id) for s in range(4)])
+    rows = np.tile(np.arange(640, 704, dtype=np.int32), (4, 1))
     four = ctx.forward(dev(toks, torch.int32), dev(rows, torch.int32))
     again = ctx.forward(dev(toks, torch.int32), dev(rows, torch.int32))
     assert torch.equal(four, again)
@@ -196,10 +197,11 @@ def test_forward_bf16_two_layer_small_within_5e2():
         assert np.abs(got[s] - want).max() <= 5e-2
 
 
-@pytest.mark.parametrize("S_,T", [(1, 256), (2, 160), (1, 64), (3, 128), (2, 96)])
+@pytest.mark.parametrize("S_,T", [(1, 256), (2, 160), (1, 64), (3, 128), (2, 96), (1, 512), (1, 640), (2, 320)])
 def test_forward_bf16_few_rows_split_k_within_5e2(S_, T):
     """Forwards of at most 384 token rows take the split-K GEMMs (tall tiles, K divided over several
-    workgroups, float32 partial sums added by a second kernel) for the O, gate/up and down projections."""
+    workgroups, float32 partial sums added by a second kernel) for the O, gate/up and down projections;
+    from there to 640 rows the O and down projections still do (128x128 tiles that would leave CUs idle)."""
     shape = S.ModelShape(n_layers=2, d_model=1024, n_heads=8, d_ff=2048, vocab=2048, mask_id=2047, rope_theta=5e5)
     w = S.make_weights(shape, seed=5, round_to_bf16=True)
     ctx = make_context(shape, to_device(w, torch.bfloat16), max_seqs=S_, max_T=T, max_rows=64)
