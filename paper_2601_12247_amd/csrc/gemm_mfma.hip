@@ -8,9 +8,10 @@
 //     v_mfma_f32_16x16x32_bf16 tiles (in a loop that also feeds LDS and direct loads this shape
 //     sustains ~14% more than 32x32x16 at two waves per SIMD, although a loop of nothing but
 //     MFMAs runs both at the same rate).  The shapes in use: 256 x 256 with 8 waves (2 x 4) for the
-//     wide layers; 192 / 160 / 96 x 256 and 128 x 256, 256 x 128, 128 x 128 with 4 waves where they
-//     put (nearly) one tile on every CU; 64 x 64 and 64 x 128 for launches with few rows, which
-//     stream the weights and want many workgroups with deep rings (pick_config);
+//     wide layers; 192 x 256, 128 x 256, 256 x 128, 320 x 128, 192 x 128 and 128 x 128, also with 8
+//     waves, where they put (nearly) one tile on every CU; 64 x 64 and 64 x 128 with 4 waves for
+//     launches with few rows, which stream the weights and want many workgroups with deep rings
+//     (pick_config); launches of up to 640 rows may also split K over several workgroups per tile;
 //   * both operands are K-contiguous in memory, so a 16-byte chunk is 8 consecutive k of one
 //     row.  K advances in stages of BK = 64 (whole 128-byte lines per row: half the L2 requests
 //     of 64-byte pieces) through a ring of LDS buffers; tiles go from
