@@ -232,37 +232,77 @@ attention_mfma_kernel(const bf16_t *__restrict__ qkv, const bf16_t *__restrict__
 // hold them) are then one 16-byte chunk.
 __device__ __forceinline__ int vt_pos(int t) { return (t & ~12) | ((t & 4) << 1) | ((t & 8) >> 1); }
 
-// Rotary embedding of q and k in place (pair (i, i + 64) of each head) and the key-contiguous
-// copy of v:  vt[canvas][head][d][vt_pos(t)] = v[canvas*T + t][head*128 + d].  One block = 64 positions
-// of one (canvas, head).
+// Rotary embedding of q and k in place (pair (i, i + 64) of each head) and the key-contiguous copy of v for 64
+// rows of one (canvas, head), by one 256-thread workgroup with 16-byte accesses throughout.
+//   base: the rows' q columns of this head (row stride 3 d);  pos(rr): canvas position of row rr;
+//   vb: vt row 0 of this (canvas, head) at the first of the 64 keys, vt_stride: keys per vt row.
+//   vb[d][vt_pos(rr)] = v[rr][d]
+template <typename PosFn>
+__device__ __forceinline__ void rope_vt_64rows(bf16_t *base, int d, const float2 *__restrict__ cos_sin, PosFn pos,
+                                               bf16_t *vb, int vt_stride, bf16_t (*tile)[64 + 2]) {
+  const int tid = threadIdx.x;
+  // rotate q and k: 64 rows x 2 tensors x 8 chunks of 8 pairs
+#pragma unroll
+  for (int it = 0; it < 4; ++it) {
+    const int idx = it * 256 + tid;
+    const int ch = idx & 7, which = (idx >> 3) & 1, rr = idx >> 4;
+    bf16_t *p = base + (int64_t)rr * 3 * d + which * d + ch * 8;
+    const float4 *cs4 = reinterpret_cast<const float4 *>(cos_sin + (int64_t)pos(rr) * 64 + ch * 8);
+    const uint4 lo = *reinterpret_cast<const uint4 *>(p), hi = *reinterpret_cast<const uint4 *>(p + 64);
+    const uint32_t lw[4] = {lo.x, lo.y, lo.z, lo.w}, hw[4] = {hi.x, hi.y, hi.z, hi.w};
+    uint32_t ol[4], oh[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const float4 c4 = cs4[e];                              // (cos, sin) of pairs 2e, 2e + 1 of the chunk
+      const float a0 = __uint_as_float(lw[e] << 16), a1 = __uint_as_float(lw[e] & 0xffff0000u);
+      const float b0 = __uint_as_float(hw[e] << 16), b1 = __uint_as_float(hw[e] & 0xffff0000u);
+      const bf16_t l0 = (bf16_t)(a0 * c4.x - b0 * c4.y), l1 = (bf16_t)(a1 * c4.z - b1 * c4.w);
+      const bf16_t h0 = (bf16_t)(b0 * c4.x + a0 * c4.y), h1 = (bf16_t)(b1 * c4.z + a1 * c4.w);
+      ol[e] = (uint32_t)__builtin_bit_cast(uint16_t, l0) | ((uint32_t)__builtin_bit_cast(uint16_t, l1) << 16);
+      oh[e] = (uint32_t)__builtin_bit_cast(uint16_t, h0) | ((uint32_t)__builtin_bit_cast(uint16_t, h1) << 16);
+    }
+    *reinterpret_cast<uint4 *>(p) = make_uint4(ol[0], ol[1], ol[2], ol[3]);
+    *reinterpret_cast<uint4 *>(p + 64) = make_uint4(oh[0], oh[1], oh[2], oh[3]);
+  }
+  // transpose v through LDS: a thread reads 8 d of one row, then writes the 8 keys of one 16-byte vt chunk
+#pragma unroll
+  for (int it = 0; it < 4; ++it) {
+    const int idx = it * 256 + tid;
+    const int rr = idx & 63, ch = idx >> 6;                  // consecutive lanes = consecutive rows: no bank conflicts
+    const uint4 v8 = *reinterpret_cast<const uint4 *>(base + (int64_t)rr * 3 * d + 2 * d + ch * 8);
+    const uint32_t w[4] = {v8.x, v8.y, v8.z, v8.w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      tile[ch * 8 + 2 * e][rr] = __builtin_bit_cast(bf16_t, (uint16_t)(w[e] & 0xffffu));
+      tile[ch * 8 + 2 * e + 1][rr] = __builtin_bit_cast(bf16_t, (uint16_t)(w[e] >> 16));
+    }
+  }
+  __syncthreads();
+#pragma unroll
+  for (int it = 0; it < 4; ++it) {
+    const int idx = it * 256 + tid;
+    const int g = idx & 7, dd = idx >> 3;                    // chunk g of vt row dd: keys 16 (g / 2) + 4 (g % 2) + {0-3, 8-11}
+    const int k0 = 16 * (g >> 1) + 4 * (g & 1);
+    uint32_t w[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const int kr = k0 + (e & 1) * 2 + (e >> 1) * 8;
+      w[e] = (uint32_t)__builtin_bit_cast(uint16_t, tile[dd][kr]) | ((uint32_t)__builtin_bit_cast(uint16_t, tile[dd][kr + 1]) << 16);
+    }
+    *reinterpret_cast<uint4 *>(vb + (int64_t)dd * vt_stride + g * 8) = make_uint4(w[0], w[1], w[2], w[3]);
+  }
+}
+
+// Full canvases: one block = 64 positions of one (canvas, head); vt[canvas][head][d][vt_pos(t)] = v[canvas*T + t][head*128 + d].
 __global__ void __launch_bounds__(256)
 rope_vt_kernel(bf16_t *__restrict__ qkv, bf16_t *__restrict__ vt, int T, int H,
                const float2 *__restrict__ cos_sin) {
   __shared__ bf16_t tile[DH][64 + 2];
   const int t0 = blockIdx.x * 64, head = blockIdx.y, seq = blockIdx.z;
   const int d = H * DH;
-  const int tid = threadIdx.x;
   bf16_t *base = qkv + ((int64_t)seq * T + t0) * 3 * d + (int64_t)head * DH;
-  // rotate q and k: 64 positions x 2 tensors x 64 pairs
-  for (int idx = tid; idx < 64 * 2 * 64; idx += 256) {
-    const int i = idx & 63, which = (idx >> 6) & 1, tt = idx >> 7;
-    bf16_t *p = base + (int64_t)tt * 3 * d + which * d;
-    const float2 cs = cos_sin[(int64_t)(t0 + tt) * 64 + i];
-    const float a = (float)p[i], b = (float)p[i + 64];
-    p[i] = (bf16_t)(a * cs.x - b * cs.y);
-    p[i + 64] = (bf16_t)(b * cs.x + a * cs.y);
-  }
-  // transpose v through LDS
-  for (int idx = tid; idx < 64 * DH; idx += 256) {
-    const int dd = idx & 127, tt = idx >> 7;
-    tile[dd][tt] = base[(int64_t)tt * 3 * d + 2 * d + dd];
-  }
-  __syncthreads();
-  bf16_t *vb = vt + ((int64_t)seq * H + head) * DH * T + t0;
-  for (int idx = tid; idx < DH * 64; idx += 256) {
-    const int tt = idx & 63, dd = idx >> 6;
-    vb[(int64_t)dd * T + vt_pos(tt)] = tile[dd][tt];
-  }
+  rope_vt_64rows(base, d, cos_sin, [&](int rr) { return t0 + rr; },
+                 vt + ((int64_t)seq * H + head) * DH * T + t0, T, tile);
 }
 
 // Window rows: rotary embedding at the rows' own canvas positions (row_pos, -1 = padding row,
@@ -274,28 +314,10 @@ rope_vt_rows_kernel(bf16_t *__restrict__ qkv, bf16_t *__restrict__ vt, const int
   __shared__ bf16_t tile[DH][64 + 2];
   const int r0 = blockIdx.x * 64, head = blockIdx.y, seq = blockIdx.z;
   const int d = H * DH;
-  const int tid = threadIdx.x;
   bf16_t *base = qkv + ((int64_t)seq * R + r0) * 3 * d + (int64_t)head * DH;
-  for (int idx = tid; idx < 64 * 2 * 64; idx += 256) {
-    const int i = idx & 63, which = (idx >> 6) & 1, rr = idx >> 7;
-    int pos = row_pos[(int64_t)seq * R + r0 + rr];
-    if (pos < 0) pos = T - 1;
-    bf16_t *p = base + (int64_t)rr * 3 * d + which * d;
-    const float2 cs = cos_sin[(int64_t)pos * 64 + i];
-    const float a = (float)p[i], b = (float)p[i + 64];
-    p[i] = (bf16_t)(a * cs.x - b * cs.y);
-    p[i + 64] = (bf16_t)(b * cs.x + a * cs.y);
-  }
-  for (int idx = tid; idx < 64 * DH; idx += 256) {
-    const int dd = idx & 127, rr = idx >> 7;
-    tile[dd][rr] = base[(int64_t)rr * 3 * d + 2 * d + dd];
-  }
-  __syncthreads();
-  bf16_t *vb = vt + ((int64_t)seq * H + head) * DH * R + r0;
-  for (int idx = tid; idx < DH * 64; idx += 256) {
-    const int rr = idx & 63, dd = idx >> 6;
-    vb[(int64_t)dd * R + vt_pos(rr)] = tile[dd][rr];
-  }
+  rope_vt_64rows(base, d, cos_sin,
+                 [&](int rr) { const int pos = row_pos[(int64_t)seq * R + r0 + rr]; return pos < 0 ? T - 1 : pos; },
+                 vt + ((int64_t)seq * H + head) * DH * R + r0, R, tile);
 }
 
 }  // namespace
