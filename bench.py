@@ -36,7 +36,7 @@ LOGIT_SCALE = 12.0             # calibrated once: K=0 decoding of this model lan
 # HBM-side bytes per launch (L2 fills + write-backs) from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE passes over
 # this script, scaled by what the counters read for a plain 256 MiB copy; the passes and the arithmetic are in
 # profiles/bench_c3_llada8b_pmc_hbm_traffic.txt
-TRAFFIC_GEMM = 408.4e6         # mean over the GEMM launches of the timed mix (algorithmic: 178.4e6)
+TRAFFIC_GEMM = 412.0e6         # mean over the GEMM launches of the timed mix (algorithmic: 179.4e6)
 TRAFFIC_STAGE1 = 518.5e6       # [2048, 126464] bf16 logits (algorithmic: 518.0e6)
 
 
