@@ -91,7 +91,7 @@ def test_rope_attention(S_, T, H, dh, theta, dtype):
 
 
 @pytest.mark.parametrize("S_,T,H", [(5, 512, 32), (9, 1280, 32), (3, 512, 32), (1, 64, 2), (3, 96, 2), (2, 320, 4),
-                                    (1, 1280, 6), (7, 160, 8)])
+                                    (1, 1280, 6), (7, 160, 8), (1, 512, 32), (2, 512, 32), (4, 512, 32), (1, 128, 4)])
 def test_qkv_attention_fused_epilogue_equals_separate_passes(S_, T, H):
     """The projection whose epilogue rotates q, k and writes the key-contiguous v, followed by the
     attention kernel, against pvf_gemm + pvf_rope_attention (rotation as a pass of its own)."""
