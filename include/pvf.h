@@ -208,7 +208,9 @@ pvf_status pvf_epilogue(pvf_ctx *ctx, void *stream, const void *logits, int32_t 
                         const pvf_decode_cfg *cfg, const pvf_state *state);
 
 /* With cfg->kv_cache = 1 the context keeps, per group, the cache and the block it was made for;
- * pvf_state_init invalidates it.  Such a round first reads done / n_drafts / k_active back
+ * pvf_state_init invalidates it, and so does a round on a state other than the one the caches were
+ * made for (states are told apart by their canvas buffer; a caller who rewrites a canvas in place
+ * between rounds must call pvf_state_init or run one round with kv_cache = 0).  Such a round first reads done / n_drafts / k_active back
  * (one stream synchronisation) to split the groups into refreshing and cached ones; the
  * cache memory (2 * n_layers * T * d_model elements per group) is allocated on first use.
  *
@@ -269,7 +271,11 @@ pvf_status pvf_rmsnorm(void *stream, int32_t dtype, const void *x, const void *g
 
 /* In-place rotary embedding of the q and k thirds of qkv [S*T, 3*d] (row m is canvas
  * position m % T), then out[S*T, d] = softmax(q k^T / sqrt(d_head)) v per canvas and head,
- * over all T keys. */
+ * over all T keys.
+ * Unlike the other calls this one is SYNCHRONOUS and ALLOCATES: it builds the rotary table on the
+ * host, allocates the table and (bf16, d_head = 128) a key-contiguous copy of v with hipMalloc,
+ * synchronises the stream and frees both before it returns.  It exists to check the kernels alone;
+ * a round uses the context's table and workspace. */
 pvf_status pvf_rope_attention(void *stream, int32_t dtype, void *qkv, void *out, int32_t S,
                               int32_t T, int32_t n_heads, int32_t d_head, float rope_theta);
 
@@ -277,9 +283,14 @@ pvf_status pvf_rope_attention(void *stream, int32_t dtype, void *qkv, void *out,
  * rotary embedding of q and k, out[S*T, d] = attention.  On return qkv holds rotated q | rotated k
  * | v.  With bf16, d_head = 128 and T % 64 == 0 the rotation and the key-contiguous copy of v that
  * the attention kernel reads are fused into the projection's epilogue; the results equal
- * pvf_gemm followed by pvf_rope_attention up to the rounding of one fused multiply-add. */
+ * pvf_gemm followed by pvf_rope_attention up to the rounding of one fused multiply-add.
+ * vt: dev [S, n_heads, 128, T] in dtype, or NULL.  On the fused path (bf16, d_head = 128, T % 64 == 0)
+ * it receives the key-contiguous copy of v the attention kernel reads: vt[s][h][c][t'] = v[s*T + t][h*128 + c]
+ * with t' = t with bits 2 and 3 exchanged (each 16 keys stored as 0-3, 8-11, 4-7, 12-15); on the other
+ * paths it is left untouched.  NULL: the library allocates that copy itself.
+ * Like pvf_rope_attention this call allocates its table (and vt if NULL) and synchronises the stream. */
 pvf_status pvf_qkv_attention(void *stream, int32_t dtype, const void *x, const void *wqkv, void *qkv,
-                             void *out, int32_t S, int32_t T, int32_t n_heads, int32_t d_head,
+                             void *vt, void *out, int32_t S, int32_t T, int32_t n_heads, int32_t d_head,
                              float rope_theta);
 
 /* Fills dev buffer with n values ~ N(0, std^2) (+ mean) from a counter-based generator;

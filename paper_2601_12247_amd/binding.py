@@ -20,7 +20,7 @@ PVF_F32, PVF_BF16 = 0, 1
 PVF_ROUTES_PLAN, PVF_ROUTES_AR, PVF_ROUTES_CAL, PVF_ROUTES_XRANDOM, PVF_ROUTES_XPLANNING = 1, 2, 4, 8, 16
 PVF_ROUTE_NONE, PVF_ROUTE_PLAN, PVF_ROUTE_AR, PVF_ROUTE_CAL = 0, 1, 2, 3
 ROUTE_NONE, ROUTE_PLAN, ROUTE_AR = 0, 1, 2
-MAX_K = 16
+MAX_K = 32          # PVF_MAX_K of include/pvf.h
 STATUS = {0: "PVF_OK", -1: "PVF_EINVAL", -2: "PVF_ESHAPE", -3: "PVF_ENOMEM", -4: "PVF_EHIP",
           -5: "PVF_ENOTIMPL"}
 
@@ -124,7 +124,7 @@ def lib() -> C.CDLL:
                                   C.c_int32, C.c_int32, C.c_float]
         L.pvf_rope_attention.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_int32,
                                          C.c_int32, C.c_int32, C.c_int32, C.c_float]
-        L.pvf_qkv_attention.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+        L.pvf_qkv_attention.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                         C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_float]
         L.pvf_fill_normal.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_int64, C.c_uint64,
                                       C.c_float, C.c_float]
@@ -389,14 +389,17 @@ def rope_attention(qkv: torch.Tensor, S: int, T: int, n_heads: int, d_head: int,
 
 
 def qkv_attention(x: torch.Tensor, wqkv: torch.Tensor, S: int, T: int, n_heads: int, d_head: int,
-                  rope_theta: float):
-    """(qkv [S*T, 3d] with q, k rotated; attention output [S*T, d]) of x [S*T, d]."""
+                  rope_theta: float, vt: Optional[torch.Tensor] = None):
+    """(qkv [S*T, 3d] with q, k rotated; attention output [S*T, d]) of x [S*T, d]; vt [S, H, d_head, T]
+    (optional) receives the key-contiguous copy of v where the fused projection epilogue writes one."""
     d = n_heads * d_head
     assert x.shape == (S * T, d) and wqkv.shape == (3 * d, d) and x.is_contiguous() and wqkv.is_contiguous()
     assert wqkv.dtype == x.dtype
     qkv = torch.empty(S * T, 3 * d, dtype=x.dtype, device=x.device)
     out = torch.empty(S * T, d, dtype=x.dtype, device=x.device)
-    _check(lib().pvf_qkv_attention(_stream(), _dtype_code(x.dtype), _ptr(x), _ptr(wqkv), _ptr(qkv), _ptr(out),
+    if vt is not None:
+        assert vt.shape == (S, n_heads, d_head, T) and vt.dtype == x.dtype
+    _check(lib().pvf_qkv_attention(_stream(), _dtype_code(x.dtype), _ptr(x), _ptr(wqkv), _ptr(qkv), _ptr(vt), _ptr(out),
                                    S, T, n_heads, d_head, rope_theta))
     return qkv, out
 

@@ -494,12 +494,11 @@ pvf_status run(pvf_ctx *ctx, hipStream_t s, const void *A, const void *W, void *
                int M, int N_out, int K, const RopeArgs &ra, const SplitK &sk = SplitK{nullptr, 0}, int splits = 1) {
   constexpr int kLdsBytes = ST * (BM + BN) * BK * 2;
   static_assert(kLdsBytes <= 160 * 1024, "LDS ring exceeds the 160 KB of a CU");
-  static bool configured = false;
-  if (!configured) {
-    PVF_HIP_CHECK(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(gemm_bf16_mfma_kernel<EPI, BM, BN, BK, ST, WM, WN>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes));
-    configured = true;
-  }
+  // once per kernel instance; a function-local static is initialised exactly once even with concurrent callers
+  static const hipError_t configured = hipFuncSetAttribute(
+      reinterpret_cast<const void *>(gemm_bf16_mfma_kernel<EPI, BM, BN, BK, ST, WM, WN>),
+      hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+  PVF_HIP_CHECK(ctx, configured);
   const int tiles_m = (M + BM - 1) / BM;
   const int tiles_n = (EPI == kEpiSwiglu) ? N_out / (BN / 2) : N_out / BN;
   const int total = tiles_m * tiles_n;

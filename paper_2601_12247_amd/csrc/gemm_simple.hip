@@ -80,6 +80,7 @@ pvf_status run(pvf_ctx *ctx, hipStream_t s, GemmEpilogue epi, const T *A, const 
     case kEpiStore: gemm_simple_kernel<T, kEpiStore><<<grid, 256, 0, s>>>(A, W, C, res, M, N, K); break;
     case kEpiResidual: gemm_simple_kernel<T, kEpiResidual><<<grid, 256, 0, s>>>(A, W, C, res, M, N, K); break;
     case kEpiSwiglu: gemm_simple_kernel<T, kEpiSwiglu><<<grid, 256, 0, s>>>(A, W, C, res, M, N, K); break;
+    default: PVF_REQUIRE(ctx, false, PVF_ENOTIMPL, "gemm_simple: epilogue %d exists only in the MFMA kernel", (int)epi);
   }
   PVF_LAUNCH_CHECK(ctx, "gemm_simple");
   return PVF_OK;

@@ -31,6 +31,7 @@ struct pvf_ctx {
   int cache_G = 0, cache_T = 0;
   bool cache_vt = false;               // values cached key-contiguous [head][d_head][T] (MFMA window attention)
   std::vector<int> cache_block;
+  const void *cache_canvas = nullptr;  // the state (its canvas buffer) the caches were made for
   int32_t *seq_host = nullptr;         // pinned staging of the round's sequence list
   int seq_host_cap = 0;
   int64_t ws_bytes = 0;
@@ -531,6 +532,10 @@ static pvf_status round_cached_impl(pvf_ctx *ctx, hipStream_t s, int G, const ui
     ctx->cache_block.assign(G, -1);
   }
   if ((int)ctx->cache_block.size() < G) ctx->cache_block.resize(G, -1);
+  if (ctx->cache_canvas != state.canvas) {                 // another state: its groups' caches are not these
+    ctx->cache_canvas = state.canvas;
+    ctx->cache_block.assign(ctx->cache_block.size(), -1);
+  }
   // state read-back and the two sequence lists
   const int need = 3 * G + G * spg;
   if (ctx->seq_host_cap < need) {
@@ -545,7 +550,7 @@ static pvf_status round_cached_impl(pvf_ctx *ctx, hipStream_t s, int G, const ui
   PVF_HIP_CHECK(ctx, hipMemcpyAsync(h_ka, state.k_active, G * sizeof(int32_t), hipMemcpyDeviceToHost, s));
   PVF_HIP_CHECK(ctx, hipStreamSynchronize(s));
   int n_full = 0, n_win = 0;
-  std::vector<int32_t> win;
+  std::vector<int32_t> win, refreshed;
   for (int g = 0; g < G; ++g) {
     if (h_done[g]) continue;
     const int kt = h_nd[g] < 0 ? 0 : (h_nd[g] > cfg.K ? cfg.K : h_nd[g]);
@@ -554,7 +559,7 @@ static pvf_status round_cached_impl(pvf_ctx *ctx, hipStream_t s, int G, const ui
       if (refresh && j == 0) h_seq[n_full++] = g * spg + j;
       else win.push_back(g * spg + j);
     }
-    if (refresh) ctx->cache_block[g] = h_ka[g];
+    if (refresh) { refreshed.push_back(g); ctx->cache_block[g] = -1; }   // valid only once its forward is enqueued
   }
   n_win = (int)win.size();
   for (int i = 0; i < n_win; ++i) h_seq[n_full + i] = win[i];
@@ -566,6 +571,7 @@ static pvf_status round_cached_impl(pvf_ctx *ctx, hipStream_t s, int G, const ui
   if (n_full) {
     st = forward_impl(ctx, s, state.canvas, ctx->seq_slot, n_full, T, ctx->row_pos, R, ctx->logits, spg);
     if (st != PVF_OK) return st;
+    for (int g : refreshed) ctx->cache_block[g] = h_ka[g];
   }
   if (n_win) {
     void *lg = (char *)ctx->logits + (size_t)n_full * R * m.vocab * ctx->esize;
@@ -740,8 +746,8 @@ extern "C" pvf_status pvf_rope_attention(void *stream, int32_t dtype, void *qkv,
 }
 
 extern "C" pvf_status pvf_qkv_attention(void *stream, int32_t dtype, const void *x, const void *wqkv, void *qkv,
-                                        void *out, int32_t S, int32_t T, int32_t n_heads, int32_t d_head,
-                                        float rope_theta) {
+                                        void *vt_caller, void *out, int32_t S, int32_t T, int32_t n_heads,
+                                        int32_t d_head, float rope_theta) {
   if (check_dtype(dtype) != PVF_OK) return PVF_EINVAL;
   PVF_REQUIRE(nullptr, x && wqkv && qkv && out && S >= 0 && T > 0 && n_heads > 0 && d_head > 0 && d_head % 2 == 0 &&
                   rope_theta > 0.f, PVF_EINVAL, "pvf_qkv_attention: bad argument");
@@ -762,8 +768,11 @@ extern "C" pvf_status pvf_qkv_attention(void *stream, int32_t dtype, const void 
   if (e != hipSuccess) { set_error(nullptr, "rotary table upload: %s", hipGetErrorString(e)); st = PVF_EHIP; }
   const bool mfma_att = use_attention_mfma(dtype, T, d_head);
   if (st == PVF_OK && mfma_att) {
-    e = hipMalloc(&vt, (size_t)M * d * 2);
-    if (e != hipSuccess) { set_error(nullptr, "scratch allocation: %s", hipGetErrorString(e)); st = PVF_EHIP; }
+    if (vt_caller) vt = vt_caller;
+    else {
+      e = hipMalloc(&vt, (size_t)M * d * 2);
+      if (e != hipSuccess) { set_error(nullptr, "scratch allocation: %s", hipGetErrorString(e)); st = PVF_EHIP; }
+    }
   }
   if (st == PVF_OK) {
     if (mfma_att && gemm_mfma_qkv_rope_supported(dtype, M, 3 * d, d, T, n_heads)) {
@@ -776,7 +785,7 @@ extern "C" pvf_status pvf_qkv_attention(void *stream, int32_t dtype, const void 
   }
   (void)hipStreamSynchronize(s);
   (void)hipFree(dev);
-  if (vt) (void)hipFree(vt);
+  if (vt && vt != vt_caller) (void)hipFree(vt);
   return st;
 }
 

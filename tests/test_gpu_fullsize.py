@@ -7,8 +7,10 @@ grid), on outputs the oracle can compute one by one:
     M = 512: sampled output elements against float64 dot products of the same bf16 inputs;
   * RoPE + attention at 32 heads, T = 512 and 1280: sampled (canvas, head, query) rows;
   * stage 1 on bf16 logits [8 x 256, 126464]: every row against the oracle;
-  * a 2-layer model at the full widths (d 4096, ff 12288, vocab 126464), bf16: logits of the
-    window rows within 5e-2 of the oracle's;
+  * a 2-layer model at the full widths (d 4096, ff 12288, vocab 126464), bf16, 2 canvases of 256 tokens
+    (the few-row tile shapes and split-K): logits of the window rows within rms 1.5e-2 / max 8e-2 of the
+    oracle's, the bound that replaces 5e-2 max-abs at this width (derived in test_gpu_bench_shapes.py,
+    which also covers the launch shapes of the benchmark rounds);
   * a complete PVF decode of the benchmark workload: structural properties that hold for any
     weights (no mask left, prompt untouched, every token committed once, K = 0 commits by the
     threshold only, determinism).
@@ -101,7 +103,7 @@ def test_stage1_full_epilogue_workload_every_row():
     np.testing.assert_allclose(conf.cpu().numpy(), p, rtol=5e-6)
 
 
-def test_two_layer_full_width_bf16_forward_within_5e2():
+def test_two_layer_full_width_bf16_forward_rms_1p5e2_max_8e2():
     shape = S.ModelShape(n_layers=2, d_model=D, n_heads=32, d_ff=FF, vocab=V, mask_id=126336, rope_theta=5e5)
     w = S.make_weights(shape, seed=21, round_to_bf16=True)
     ctx = make_context(shape, to_device(w, torch.bfloat16), max_seqs=2, max_T=256, max_rows=64)
@@ -116,14 +118,11 @@ def test_two_layer_full_width_bf16_forward_within_5e2():
         rms = float((got[s] - want).std())
         print(f"canvas {s}: logit error rms = {rms:.4f}, max = {err:.4f} over {want.size} logits "
               f"(logit std {want.std():.3f})")
-        # At the full widths the 5e-2 max-abs bar (met by the reduced-width model in
-        # test_gpu_forward.py) is a statistical extreme: every activation tensor that feeds an MFMA
-        # (normed input, q/k/v, rotated q/k, attention output, SwiGLU output, residual stream, final
-        # hidden rows) is stored in bf16, i.e. ~9 roundings of 2^-9 relative per layer.  Emulating
-        # exactly those roundings inside the float64 oracle gives an rms logit error of 1.3e-2 for
-        # this model (the GPU measures 1.2e-2), and the largest of 8.1 million such errors sits at
-        # ~5.4 rms = 6.6e-2.  The test therefore bounds the rms (which a wrong kernel would blow up)
-        # and the maximum at 6.5 rms.
+        # At the full widths the 5e-2 max-abs bar (met by the reduced-width model in test_gpu_forward.py)
+        # is a statistical extreme of bf16 storage itself: tests/bf16_emulation.py, the float64 forward
+        # with only the round-to-bf16 of each stored activation, sits at rms ~1.3e-2 / max ~6e-2 from
+        # the oracle (asserted in test_gpu_bench_shapes.py).  So the rms, which a wrong kernel would
+        # blow up, and the maximum at ~6 rms are bounded instead.
         assert rms <= 1.5e-2
         assert err <= 8e-2
         # the decisions stage 1 takes on these logits agree wherever the oracle's top-2 gap exceeds the error
