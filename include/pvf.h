@@ -279,6 +279,17 @@ pvf_status pvf_rmsnorm(void *stream, int32_t dtype, const void *x, const void *g
 pvf_status pvf_rope_attention(void *stream, int32_t dtype, void *qkv, void *out, int32_t S,
                               int32_t T, int32_t n_heads, int32_t d_head, float rope_theta);
 
+/* pvf_rope_attention for callers that cannot allocate (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc): same arguments and results, but the rotary table and the
+ * key-contiguous copy of v live in a static device array of the library (17 MiB per GPU, held until
+ * the process ends), the table is computed by a kernel on `stream`, and the call neither allocates,
+ * frees nor synchronises.  Limits: T <= 2048, d_head <= 128, and on the bf16 / d_head = 128 path
+ * S*T*n_heads*d_head <= 8 Mi elements; beyond them PVF_ESHAPE.  All calls on one GPU share that
+ * array: calls that overlap on one GPU (different streams or threads) race; calls on one stream
+ * are ordered and each rewrites everything it reads. */
+pvf_status pvf_rope_attention_noalloc(void *stream, int32_t dtype, void *qkv, void *out, int32_t S,
+                                      int32_t T, int32_t n_heads, int32_t d_head, float rope_theta);
+
 /* The attention half of a layer as the forward runs it: qkv[S*T, 3*d] = x[S*T, d] * wqkv[3*d, d]^T,
  * rotary embedding of q and k, out[S*T, d] = attention.  On return qkv holds rotated q | rotated k
  * | v.  With bf16, d_head = 128 and T % 64 == 0 the rotation and the key-contiguous copy of v that

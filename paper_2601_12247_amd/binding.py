@@ -29,7 +29,7 @@ EXPORTS = ["pvf_create", "pvf_destroy", "pvf_last_error", "pvf_workspace_bytes",
            "pvf_profile_end", "pvf_forward",
            "pvf_epilogue", "pvf_round", "pvf_state_init", "pvf_decode", "pvf_stage1", "pvf_gemm",
            "pvf_gemm_swiglu", "pvf_rmsnorm", "pvf_rope_attention", "pvf_fill_normal", "pvf_entropy",
-           "pvf_plan_vocab_select", "pvf_qkv_attention"]
+           "pvf_plan_vocab_select", "pvf_qkv_attention", "pvf_rope_attention_noalloc"]
 
 
 class PvfError(RuntimeError):
@@ -124,6 +124,7 @@ def lib() -> C.CDLL:
                                   C.c_int32, C.c_int32, C.c_float]
         L.pvf_rope_attention.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_int32,
                                          C.c_int32, C.c_int32, C.c_int32, C.c_float]
+        L.pvf_rope_attention_noalloc.argtypes = L.pvf_rope_attention.argtypes
         L.pvf_qkv_attention.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                         C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_float]
         L.pvf_fill_normal.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_int64, C.c_uint64,
@@ -385,6 +386,16 @@ def rope_attention(qkv: torch.Tensor, S: int, T: int, n_heads: int, d_head: int,
     out = torch.empty(S * T, n_heads * d_head, dtype=qkv.dtype, device=qkv.device)
     _check(lib().pvf_rope_attention(_stream(), _dtype_code(qkv.dtype), _ptr(qkv), _ptr(out), S, T,
                                     n_heads, d_head, rope_theta))
+    return out
+
+
+def rope_attention_noalloc(qkv: torch.Tensor, out: torch.Tensor, S: int, T: int, n_heads: int, d_head: int,
+                           rope_theta: float) -> torch.Tensor:
+    """pvf_rope_attention_noalloc: like rope_attention, into the caller's `out`; the library allocates nothing."""
+    assert qkv.shape == (S * T, 3 * n_heads * d_head) and qkv.is_contiguous()
+    assert out.shape == (S * T, n_heads * d_head) and out.dtype == qkv.dtype
+    _check(lib().pvf_rope_attention_noalloc(_stream(), _dtype_code(qkv.dtype), _ptr(qkv), _ptr(out), S, T,
+                                            n_heads, d_head, rope_theta))
     return out
 
 

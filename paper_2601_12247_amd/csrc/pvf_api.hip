@@ -7,6 +7,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <string>
 #include <vector>
 
@@ -743,6 +744,76 @@ extern "C" pvf_status pvf_rope_attention(void *stream, int32_t dtype, void *qkv,
   (void)hipFree(dev);
   if (vt) (void)hipFree(vt);
   return st;
+}
+
+// ---- the variant of pvf_rope_attention that allocates nothing ---------------------------------
+// Its rotary table and the key-contiguous copy of v live in one file-scope device array.  Each GPU
+// holds its own copy of the array at its own address, looked up once per device (with that device
+// current) and kept; host code only ever uses the looked-up pointer, never the array's name.
+namespace {
+constexpr int kNoAllocMaxT = 2048, kNoAllocMaxHalf = 64;
+constexpr size_t kNoAllocTabBytes = (size_t)kNoAllocMaxT * kNoAllocMaxHalf * sizeof(float2);   // 1 MiB
+constexpr size_t kNoAllocVtBytes = (size_t)16 << 20;                                            // 16 MiB
+static __device__ __align__(256) unsigned char scratch[kNoAllocTabBytes + kNoAllocVtBytes];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+unsigned char *g_scratch_ptr[kMaxDevices] = {nullptr};
+
+struct InvFreq { double v[kNoAllocMaxHalf]; };
+
+// tab[t][i] = (cos, sin)(t * inv_freq[i]) evaluated in double precision, like the host-built table
+__global__ void __launch_bounds__(256) rope_table_kernel(float2 *tab, int T, int half, InvFreq f) {
+  const int idx = blockIdx.x * 256 + threadIdx.x;
+  if (idx >= T * half) return;
+  const double a = (double)(idx / half) * f.v[idx % half];
+  tab[idx] = make_float2((float)cos(a), (float)sin(a));
+}
+
+pvf_status scratch_of_current_device(unsigned char **out) {
+  int dev = -1;
+  PVF_HIP_CHECK(nullptr, hipGetDevice(&dev));
+  PVF_REQUIRE(nullptr, dev >= 0 && dev < kMaxDevices, PVF_ESHAPE, "device index %d outside [0,%d)", dev, kMaxDevices);
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void *p = nullptr;
+    PVF_HIP_CHECK(nullptr, hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    PVF_REQUIRE(nullptr, p != nullptr, PVF_EHIP, "hipGetSymbolAddress returned a NULL address");
+    g_scratch_ptr[dev] = (unsigned char *)p;
+  }
+  *out = g_scratch_ptr[dev];
+  return PVF_OK;
+}
+}  // namespace
+
+extern "C" pvf_status pvf_rope_attention_noalloc(void *stream, int32_t dtype, void *qkv, void *out, int32_t S,
+                                                 int32_t T, int32_t n_heads, int32_t d_head, float rope_theta) {
+  if (check_dtype(dtype) != PVF_OK) return PVF_EINVAL;
+  PVF_REQUIRE(nullptr, qkv && out && S >= 0 && T > 0 && n_heads > 0 && d_head > 0 && d_head % 2 == 0 && rope_theta > 0.f,
+              PVF_EINVAL, "pvf_rope_attention_noalloc: bad argument");
+  const int half = d_head / 2;
+  PVF_REQUIRE(nullptr, T <= kNoAllocMaxT && half <= kNoAllocMaxHalf, PVF_ESHAPE,
+              "pvf_rope_attention_noalloc: T=%d d_head=%d exceed the static scratch (T <= %d, d_head <= %d)", T, d_head,
+              kNoAllocMaxT, 2 * kNoAllocMaxHalf);
+  const bool mfma = use_attention_mfma(dtype, T, d_head);
+  const size_t vt_bytes = mfma ? (size_t)S * T * n_heads * d_head * 2 : 0;
+  PVF_REQUIRE(nullptr, vt_bytes <= kNoAllocVtBytes, PVF_ESHAPE,
+              "pvf_rope_attention_noalloc: S*T*n_heads*d_head = %lld elements exceed the static scratch (%lld)",
+              (long long)S * T * n_heads * d_head, (long long)(kNoAllocVtBytes / 2));
+  if (S == 0) return PVF_OK;
+  unsigned char *base = nullptr;
+  pvf_status st = scratch_of_current_device(&base);
+  if (st != PVF_OK) return st;
+  hipStream_t s = (hipStream_t)stream;
+  float2 *tab = reinterpret_cast<float2 *>(base);
+  void *vt = base + kNoAllocTabBytes;
+  InvFreq f;
+  for (int i = 0; i < half; ++i) f.v[i] = std::pow((double)rope_theta, -2.0 * i / d_head);
+  for (int i = half; i < kNoAllocMaxHalf; ++i) f.v[i] = 0.0;
+  rope_table_kernel<<<(T * half + 255) / 256, 256, 0, s>>>(tab, T, half, f);
+  PVF_LAUNCH_CHECK(nullptr, "rope_table");
+  // every element of tab[0, T*half) and of the vt region the attention reads is rewritten by this call
+  return launch_rope_attention(nullptr, s, dtype, qkv, vt, out, S, T, n_heads, d_head, tab);
 }
 
 extern "C" pvf_status pvf_qkv_attention(void *stream, int32_t dtype, const void *x, const void *wqkv, void *qkv,
