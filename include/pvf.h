@@ -177,10 +177,14 @@ int64_t pvf_workspace_bytes(const pvf_ctx *ctx);
 
 /* ---- per-kernel timing ------------------------------------------------------------------
  * Between pvf_profile_begin and pvf_profile_end every GEMM, attention (rotary + attention) and
- * epilogue stage-1 launch the context makes is bracketed by a pair of HIP events on the launch
- * stream.  pvf_profile_end synchronises the stream and returns, per category, the summed
+ * epilogue stage-1 launch the context makes, and per round the whole forward and stage 2, are
+ * bracketed by a pair of HIP events on the launch stream (about 6 us of host time per pair: time
+ * throughput in a pass without it).  pvf_profile_end synchronises the stream and returns, per category, the summed
  * event-to-event time, the algorithmic work (flops / bytes) and the number of launches. */
-enum { PVF_PROF_GEMM = 0, PVF_PROF_ATTENTION = 1, PVF_PROF_STAGE1 = 2, PVF_PROF_NCAT = 3 };
+enum { PVF_PROF_GEMM = 0, PVF_PROF_ATTENTION = 1, PVF_PROF_STAGE1 = 2,
+       PVF_PROF_FORWARD = 3,   /* the whole batched forward of a round (encloses the GEMM and attention launches) */
+       PVF_PROF_STAGE2 = 4,    /* verify / commit / propose + next canvases */
+       PVF_PROF_NCAT = 5 };
 typedef struct {
   double ms[PVF_PROF_NCAT], flops[PVF_PROF_NCAT], bytes[PVF_PROF_NCAT];
   int64_t launches[PVF_PROF_NCAT];
@@ -221,13 +225,20 @@ pvf_status pvf_epilogue(pvf_ctx *ctx, void *stream, const void *logits, int32_t 
 pvf_status pvf_round(pvf_ctx *ctx, void *stream, int32_t G, const uint32_t *plan_bitmap,
                      const pvf_decode_cfg *cfg, const pvf_state *state, int32_t n_seq_host);
 
+/* pvf_round, then the per-group status words read back with ONE copy and the stream synchronised:
+ * status_host (host, 5*G int32) = { done, n_drafts, n_commit[0..2] } of every group after the round.
+ * sum over live groups of 1 + n_drafts is the next round's n_seq_host.  pvf_decode loops over this. */
+pvf_status pvf_round_sync(pvf_ctx *ctx, void *stream, int32_t G, const uint32_t *plan_bitmap,
+                          const pvf_decode_cfg *cfg, const pvf_state *state, int32_t n_seq_host,
+                          int32_t *status_host);
+
 /* y_0 = [prompt | MASK^gen_len] in every slot, no drafts, k_active = 0, n_ws_blocks = 1, done = 0.
  *   prompt dev int32 [G, prompt_len]; must not contain mask_id (not checked on device). */
 pvf_status pvf_state_init(pvf_ctx *ctx, void *stream, const int32_t *prompt, int32_t G,
                           const pvf_decode_cfg *cfg, const pvf_state *state);
 
 /* Algorithm 1 to completion for G groups: pvf_state_init, then pvf_round until every group
- * is done.  Synchronises the stream once per round to read 2*G status words.
+ * is done.  Synchronises the stream once per round to read 5*G status words (one copy).
  *   out_tokens dev int32 [G, T]; stats host (may be NULL). */
 pvf_status pvf_decode(pvf_ctx *ctx, void *stream, const int32_t *prompt, int32_t G,
                       const uint32_t *plan_bitmap, const pvf_decode_cfg *cfg,

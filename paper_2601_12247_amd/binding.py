@@ -29,7 +29,7 @@ EXPORTS = ["pvf_create", "pvf_destroy", "pvf_last_error", "pvf_workspace_bytes",
            "pvf_profile_end", "pvf_forward",
            "pvf_epilogue", "pvf_round", "pvf_state_init", "pvf_decode", "pvf_stage1", "pvf_gemm",
            "pvf_gemm_swiglu", "pvf_rmsnorm", "pvf_rope_attention", "pvf_fill_normal", "pvf_entropy",
-           "pvf_plan_vocab_select", "pvf_qkv_attention", "pvf_rope_attention_noalloc"]
+           "pvf_plan_vocab_select", "pvf_qkv_attention", "pvf_rope_attention_noalloc", "pvf_round_sync"]
 
 
 class PvfError(RuntimeError):
@@ -72,9 +72,12 @@ class StatsC(C.Structure):
                 ("drafts_accepted", C.c_int64), ("ms_total", C.c_double)]
 
 
+PROF_CATEGORIES = ("gemm", "attention", "stage1", "forward", "stage2")
+
+
 class ProfileC(C.Structure):
-    _fields_ = [("ms", C.c_double * 3), ("flops", C.c_double * 3), ("bytes", C.c_double * 3),
-                ("launches", C.c_int64 * 3)]
+    _fields_ = [("ms", C.c_double * 5), ("flops", C.c_double * 5), ("bytes", C.c_double * 5),
+                ("launches", C.c_int64 * 5)]
 
 
 _lib = None
@@ -104,6 +107,8 @@ def lib() -> C.CDLL:
                                    C.POINTER(StateC)]
         L.pvf_round.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p,
                                 C.POINTER(DecodeCfgC), C.POINTER(StateC), C.c_int32]
+        L.pvf_round_sync.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p,
+                                     C.POINTER(DecodeCfgC), C.POINTER(StateC), C.c_int32, C.POINTER(C.c_int32)]
         L.pvf_state_init.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
                                      C.POINTER(DecodeCfgC), C.POINTER(StateC)]
         L.pvf_decode.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p,
@@ -280,7 +285,7 @@ class Context:
         p = ProfileC()
         _check(lib().pvf_profile_end(self.handle, _stream(), C.byref(p)), self.handle)
         return {name: {"ms": p.ms[i], "flops": p.flops[i], "bytes": p.bytes[i], "launches": p.launches[i]}
-                for i, name in enumerate(("gemm", "attention", "stage1"))}
+                for i, name in enumerate(PROF_CATEGORIES)}
 
     # ---- the four calls -------------------------------------------------------------
     def forward(self, tokens: torch.Tensor, row_pos: torch.Tensor) -> torch.Tensor:
@@ -295,6 +300,15 @@ class Context:
         cfgc, stc = state.cfg.c(), state.c()
         _check(lib().pvf_round(self.handle, _stream(), state.G, _ptr(plan_bitmap), C.byref(cfgc),
                                C.byref(stc), n_seq), self.handle)
+
+    def round_sync(self, state: State, plan_bitmap: torch.Tensor, n_seq: int = 0):
+        """pvf_round_sync: one round and its status words; returns a list of G tuples
+        (done, n_drafts, committed by threshold, by planning, by AR)."""
+        cfgc, stc = state.cfg.c(), state.c()
+        buf = (C.c_int32 * (5 * state.G))()
+        _check(lib().pvf_round_sync(self.handle, _stream(), state.G, _ptr(plan_bitmap), C.byref(cfgc),
+                                    C.byref(stc), n_seq, buf), self.handle)
+        return [tuple(buf[5 * g: 5 * g + 5]) for g in range(state.G)]
 
     def state_init(self, state: State, prompt: torch.Tensor) -> None:
         cfgc, stc = state.cfg.c(), state.c()

@@ -126,6 +126,9 @@ pvf_status launch_attention_window(pvf_ctx *ctx, hipStream_t s, int dtype, const
                                    const pvf_state &st, const int32_t *seq_slot, int n_seq, int n_heads,
                                    int d_head, void *out);
 
+// out[5 g ..] = done, n_drafts, n_commit[0..2] of group g
+pvf_status launch_pack_status(pvf_ctx *ctx, hipStream_t s, int G, const pvf_state &st, int32_t *out);
+
 pvf_status launch_copy_out(pvf_ctx *ctx, hipStream_t s, int G, int K, int T,
                            const int32_t *canvas, int32_t *out_tokens);
 

@@ -438,6 +438,22 @@ pvf_status launch_build_batch(pvf_ctx *ctx, hipStream_t s, int G, int n_seq,
   return PVF_OK;
 }
 
+__global__ void pack_status_kernel(int G, pvf_state st, int32_t *__restrict__ out) {
+  const int g = blockIdx.x * blockDim.x + threadIdx.x;
+  if (g >= G) return;
+  out[5 * g + 0] = st.done[g];
+  out[5 * g + 1] = st.n_drafts[g];
+  out[5 * g + 2] = st.n_commit[3 * g + 0];
+  out[5 * g + 3] = st.n_commit[3 * g + 1];
+  out[5 * g + 4] = st.n_commit[3 * g + 2];
+}
+
+pvf_status launch_pack_status(pvf_ctx *ctx, hipStream_t s, int G, const pvf_state &st, int32_t *out) {
+  pack_status_kernel<<<(G + 255) / 256, 256, 0, s>>>(G, st, out);
+  PVF_LAUNCH_CHECK(ctx, "pack_status");
+  return PVF_OK;
+}
+
 pvf_status launch_copy_out(pvf_ctx *ctx, hipStream_t s, int G, int K, int T,
                            const int32_t *canvas, int32_t *out_tokens) {
   copy_out_kernel<<<G, 256, 0, s>>>(K, T, canvas, out_tokens);

@@ -24,7 +24,8 @@ struct pvf_ctx {
   size_t splitk_floats = 0;
   int32_t *seq_slot = nullptr, *row_pos = nullptr;
   float2 *cos_sin = nullptr;           // [max_T, d_head/2]
-  int32_t *status_host = nullptr;      // pinned, 2*G words per round
+  int32_t *status_host = nullptr;      // pinned, 5*G words per round: done, n_drafts, n_commit[3] of each group
+  int32_t *status_dev = nullptr;       // the same words, packed on the device by one small kernel
   int status_cap = 0;
   // block-level K/V cache (decode_cfg.kv_cache): [G][n_layers][T][d] each, row-major like the
   // k / v thirds of the qkv buffer; cache_block[g] = active block the cache of group g is for
@@ -177,7 +178,7 @@ static void free_ws(pvf_ctx *c) {
   for (hipEvent_t e : c->ev_pool) (void)hipEventDestroy(e);
   c->ev_pool.clear();
   void *ptrs[] = {c->h, c->xn, c->qkv, c->att, c->act, c->vt, c->hrows, c->logits, c->seq_slot, c->row_pos, c->cos_sin,
-                  c->kcache, c->vcache, c->splitk_ws};
+                  c->kcache, c->vcache, c->splitk_ws, c->status_dev};
   for (void *p : ptrs) if (p) (void)hipFree(p);
   if (c->status_host) (void)hipHostFree(c->status_host);
   if (c->seq_host) (void)hipHostFree(c->seq_host);
@@ -453,12 +454,16 @@ extern "C" pvf_status pvf_epilogue(pvf_ctx *ctx, void *stream, const void *logit
   hipStream_t s = (hipStream_t)stream;
   const RowFilter rf = make_filter(*cfg, *state, nullptr);
   const int64_t n_rows = (int64_t)G * (1 + cfg->K) * rf.R;
-  st = launch_stage1(ctx, s, logits, logits_dtype, n_rows, vocab, mask_id, cfg->logit_scale, rf, state->conf, state->tok);
+  {
+    ProfScope ps(ctx, s, PVF_PROF_STAGE1, 0.0, (double)n_rows * vocab * (logits_dtype == PVF_BF16 ? 2.0 : 4.0));
+    st = launch_stage1(ctx, s, logits, logits_dtype, n_rows, vocab, mask_id, cfg->logit_scale, rf, state->conf, state->tok);
+  }
   if (st != PVF_OK) return st;
   if (cfg->routes & PVF_ROUTES_CAL) {
     st = launch_entropy(ctx, s, logits, logits_dtype, n_rows, vocab, mask_id, cfg->logit_scale, rf, state->ent);
     if (st != PVF_OK) return st;
   }
+  ProfScope ps(ctx, s, PVF_PROF_STAGE2, 0.0, 0.0);
   return launch_stage2(ctx, s, G, vocab, mask_id, plan_bitmap, *cfg, *state);
 }
 
@@ -491,7 +496,10 @@ static pvf_status round_impl(pvf_ctx *ctx, hipStream_t s, int G, const uint32_t 
   if (n_seq <= 0 || n_seq > all) n_seq = all;
   pvf_status st = launch_build_batch(ctx, s, G, n_seq, cfg, state, ctx->seq_slot, ctx->row_pos);
   if (st != PVF_OK) return st;
-  st = forward_impl(ctx, s, state.canvas, ctx->seq_slot, n_seq, T, ctx->row_pos, R, ctx->logits);
+  {
+    ProfScope ps(ctx, s, PVF_PROF_FORWARD, 0.0, 0.0);
+    st = forward_impl(ctx, s, state.canvas, ctx->seq_slot, n_seq, T, ctx->row_pos, R, ctx->logits);
+  }
   if (st != PVF_OK) return st;
   const RowFilter rf = make_filter(cfg, state, ctx->seq_slot);
   {
@@ -505,6 +513,7 @@ static pvf_status round_impl(pvf_ctx *ctx, hipStream_t s, int G, const uint32_t 
                         ctx->model.mask_id, cfg.logit_scale, rf, state.ent);
     if (st != PVF_OK) return st;
   }
+  ProfScope ps(ctx, s, PVF_PROF_STAGE2, 0.0, 0.0);
   return launch_stage2(ctx, s, G, ctx->model.vocab, ctx->model.mask_id, plan_bitmap, cfg, state);
 }
 
@@ -569,15 +578,18 @@ static pvf_status round_cached_impl(pvf_ctx *ctx, hipStream_t s, int G, const ui
   PVF_HIP_CHECK(ctx, hipMemcpyAsync(ctx->seq_slot, h_seq, n_seq * sizeof(int32_t), hipMemcpyHostToDevice, s));
   pvf_status st = launch_fill_row_pos(ctx, s, cfg, state, ctx->seq_slot, n_seq, ctx->row_pos);
   if (st != PVF_OK) return st;
-  if (n_full) {
-    st = forward_impl(ctx, s, state.canvas, ctx->seq_slot, n_full, T, ctx->row_pos, R, ctx->logits, spg);
-    if (st != PVF_OK) return st;
-    for (int g : refreshed) ctx->cache_block[g] = h_ka[g];
-  }
-  if (n_win) {
-    void *lg = (char *)ctx->logits + (size_t)n_full * R * m.vocab * ctx->esize;
-    st = forward_window_impl(ctx, s, cfg, state, ctx->seq_slot + n_full, n_win, ctx->row_pos + (size_t)n_full * R, lg);
-    if (st != PVF_OK) return st;
+  {
+    ProfScope ps(ctx, s, PVF_PROF_FORWARD, 0.0, 0.0);
+    if (n_full) {
+      st = forward_impl(ctx, s, state.canvas, ctx->seq_slot, n_full, T, ctx->row_pos, R, ctx->logits, spg);
+      if (st != PVF_OK) return st;
+      for (int g : refreshed) ctx->cache_block[g] = h_ka[g];
+    }
+    if (n_win) {
+      void *lg = (char *)ctx->logits + (size_t)n_full * R * m.vocab * ctx->esize;
+      st = forward_window_impl(ctx, s, cfg, state, ctx->seq_slot + n_full, n_win, ctx->row_pos + (size_t)n_full * R, lg);
+      if (st != PVF_OK) return st;
+    }
   }
   const RowFilter rf = make_filter(cfg, state, ctx->seq_slot);
   {
@@ -590,7 +602,39 @@ static pvf_status round_cached_impl(pvf_ctx *ctx, hipStream_t s, int G, const ui
     st = launch_entropy(ctx, s, ctx->logits, m.dtype, (int64_t)n_seq * R, m.vocab, m.mask_id, cfg.logit_scale, rf, state.ent);
     if (st != PVF_OK) return st;
   }
+  ProfScope ps(ctx, s, PVF_PROF_STAGE2, 0.0, 0.0);
   return launch_stage2(ctx, s, G, m.vocab, m.mask_id, plan_bitmap, cfg, state);
+}
+
+// One round, then the 5 status words of every group (done, n_drafts, n_commit[3]) packed by one small
+// kernel, copied to the context's pinned buffer with one copy, and the stream synchronised.
+static pvf_status round_status_impl(pvf_ctx *ctx, hipStream_t s, int G, const uint32_t *plan_bitmap,
+                                    const pvf_decode_cfg &cfg, const pvf_state &state, int n_seq) {
+  if (ctx->status_cap < 5 * G) {
+    if (ctx->status_host) (void)hipHostFree(ctx->status_host);
+    if (ctx->status_dev) (void)hipFree(ctx->status_dev);
+    ctx->status_host = ctx->status_dev = nullptr; ctx->status_cap = 0;
+    PVF_HIP_CHECK(ctx, hipHostMalloc((void **)&ctx->status_host, (size_t)5 * G * sizeof(int32_t), hipHostMallocDefault));
+    PVF_HIP_CHECK(ctx, hipMalloc((void **)&ctx->status_dev, (size_t)5 * G * sizeof(int32_t)));
+    ctx->status_cap = 5 * G;
+  }
+  pvf_status st = round_impl(ctx, s, G, plan_bitmap, cfg, state, n_seq);
+  if (st != PVF_OK) return st;
+  if ((st = launch_pack_status(ctx, s, G, state, ctx->status_dev)) != PVF_OK) return st;
+  PVF_HIP_CHECK(ctx, hipMemcpyAsync(ctx->status_host, ctx->status_dev, (size_t)5 * G * sizeof(int32_t), hipMemcpyDeviceToHost, s));
+  PVF_HIP_CHECK(ctx, hipStreamSynchronize(s));
+  return PVF_OK;
+}
+
+extern "C" pvf_status pvf_round_sync(pvf_ctx *ctx, void *stream, int32_t G, const uint32_t *plan_bitmap,
+                                     const pvf_decode_cfg *cfg, const pvf_state *state, int32_t n_seq_host,
+                                     int32_t *status_host) {
+  pvf_status st = check_round(ctx, G, plan_bitmap, cfg, state);
+  if (st != PVF_OK) return st;
+  PVF_REQUIRE(ctx, status_host != nullptr, PVF_EINVAL, "pvf_round_sync: status_host is NULL");
+  if ((st = round_status_impl(ctx, (hipStream_t)stream, G, plan_bitmap, *cfg, *state, n_seq_host)) != PVF_OK) return st;
+  memcpy(status_host, ctx->status_host, (size_t)5 * G * sizeof(int32_t));
+  return PVF_OK;
 }
 
 extern "C" pvf_status pvf_round(pvf_ctx *ctx, void *stream, int32_t G, const uint32_t *plan_bitmap,
@@ -618,36 +662,24 @@ extern "C" pvf_status pvf_decode(pvf_ctx *ctx, void *stream, const int32_t *prom
   if (st != PVF_OK) return st;
   PVF_REQUIRE(ctx, out_tokens && (prompt || cfg->prompt_len == 0), PVF_EINVAL, "pvf_decode: NULL pointer");
   hipStream_t s = (hipStream_t)stream;
-  if (ctx->status_cap < 5 * G) {
-    if (ctx->status_host) (void)hipHostFree(ctx->status_host);
-    ctx->status_host = nullptr;
-    PVF_HIP_CHECK(ctx, hipHostMalloc((void **)&ctx->status_host, (size_t)5 * G * sizeof(int32_t), hipHostMallocDefault));
-    ctx->status_cap = 5 * G;
-  }
-  int32_t *h_done = ctx->status_host, *h_nd = h_done + G, *h_nc = h_nd + G;
   pvf_stats acc;
   memset(&acc, 0, sizeof(acc));
   const auto t0 = std::chrono::steady_clock::now();
   ctx->cache_block.assign(ctx->cache_block.size(), -1);
   if ((st = launch_state_init(ctx, s, prompt, G, ctx->model.mask_id, *cfg, *state)) != PVF_OK) return st;
   int n_seq = G;                                  // first round: backbones only
-  std::vector<int> prev_nd(G, 0);
   const int max_rounds = cfg->gen_len + 2;        // every round commits at least one token per live group
   while (n_seq > 0) {
     PVF_REQUIRE(ctx, acc.rounds < max_rounds, PVF_EINVAL, "pvf_decode: no progress after %d rounds", acc.rounds);
-    if ((st = round_impl(ctx, s, G, plan_bitmap, *cfg, *state, n_seq)) != PVF_OK) return st;
+    if ((st = round_status_impl(ctx, s, G, plan_bitmap, *cfg, *state, n_seq)) != PVF_OK) return st;
     acc.rounds += 1;
     acc.seq_forwards += n_seq;
-    PVF_HIP_CHECK(ctx, hipMemcpyAsync(h_done, state->done, G * sizeof(int32_t), hipMemcpyDeviceToHost, s));
-    PVF_HIP_CHECK(ctx, hipMemcpyAsync(h_nd, state->n_drafts, G * sizeof(int32_t), hipMemcpyDeviceToHost, s));
-    PVF_HIP_CHECK(ctx, hipMemcpyAsync(h_nc, state->n_commit, 3 * G * sizeof(int32_t), hipMemcpyDeviceToHost, s));
-    PVF_HIP_CHECK(ctx, hipStreamSynchronize(s));
     n_seq = 0;
     for (int g = 0; g < G; ++g) {
-      acc.n_base += h_nc[3 * g + 0]; acc.n_plan += h_nc[3 * g + 1]; acc.n_ar += h_nc[3 * g + 2];
-      acc.drafts_accepted += (h_nc[3 * g + 1] > 0) + h_nc[3 * g + 2];
-      if (!h_done[g]) { n_seq += 1 + h_nd[g]; acc.drafts_proposed += h_nd[g]; }
-      prev_nd[g] = h_nd[g];
+      const int32_t *w = ctx->status_host + 5 * g;            // done, n_drafts, n_commit[3]
+      acc.n_base += w[2]; acc.n_plan += w[3]; acc.n_ar += w[4];
+      acc.drafts_accepted += (w[3] > 0) + w[4];
+      if (!w[0]) { n_seq += 1 + w[1]; acc.drafts_proposed += w[1]; }
     }
   }
   if ((st = launch_copy_out(ctx, s, G, cfg->K, cfg->prompt_len + cfg->gen_len, state->canvas, out_tokens)) != PVF_OK) return st;

@@ -13,6 +13,8 @@ from .inputs import (  # noqa: F401
     f32_to_bf16_bits,
     bf16_bits_to_f32,
     make_weights,
+    make_consistent_weights,
+    prior_plan_vocab,
     make_prompt,
     make_plan_vocab,
     plan_bitmap,

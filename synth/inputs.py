@@ -105,6 +105,34 @@ def make_weights(shape: ModelShape, seed: int = 0, std: float = 0.02,
     return w
 
 
+def make_consistent_weights(shape: ModelShape, seed: int = 0, mix: float = 1.0, std: float = 0.02,
+                            round_to_bf16: bool = False) -> Dict[str, object]:
+    """Weights of a synthetic denoiser whose predictions are self-consistent: unit-variance embeddings, output
+    head = std * embedding, and the two projections that write into the residual stream (wo, w_down) scaled
+    by `mix`; everything else as make_weights draws it.  A committed token then predicts itself at its own
+    position, and masked positions differ by what the layers mix in from the rest of the canvas."""
+    w = make_weights(shape, seed=seed, std=std, round_to_bf16=round_to_bf16)
+    rng = np.random.default_rng(seed + 100)
+    emb = rng.standard_normal((shape.vocab, shape.d_model), dtype=np.float32)
+    head = (emb * np.float32(std)).astype(np.float32)
+    w["embed"] = bf16_round(emb) if round_to_bf16 else emb
+    w["out_head"] = bf16_round(head) if round_to_bf16 else head
+    for lw in w["layers"]:
+        for name in ("wo", "w_down"):
+            m = (lw[name] * np.float32(mix)).astype(np.float32)
+            lw[name] = bf16_round(m) if round_to_bf16 else m
+    return w
+
+
+def prior_plan_vocab(w: Dict[str, object], n: int, mask_id: int) -> np.ndarray:
+    """n token ids (sorted) that the output head scores highest on the bare [MASK] embedding: the tokens such a
+    model predicts most readily at a masked position.  Stand-in for a calibrated planning vocabulary."""
+    e = np.asarray(w["embed"][mask_id], dtype=np.float64)
+    score = np.asarray(w["out_head"], dtype=np.float64) @ (e / np.sqrt(np.mean(e * e)))
+    score[mask_id] = -np.inf
+    return np.sort(np.argsort(-score, kind="stable")[:n]).astype(np.int32)
+
+
 # ----------------------------------------------------------------------------
 # prompts, planning vocabulary
 # ----------------------------------------------------------------------------

@@ -204,3 +204,67 @@ def test_round_rejects_shapes_beyond_the_context(tiny):
     with pytest.raises(B.PvfError) as e:
         ctx.round(st, bitmap)
     assert e.value.status == -2
+
+
+def test_round_sync_status_words_equal_the_state(tiny):
+    """pvf_round_sync = pvf_round + the packed per-group status read back with one copy."""
+    shape, ctx, fwd = tiny
+    cfg = B.DecodeCfg(block_len=16, prompt_len=32, gen_len=32, K=2, logit_scale=shape.logit_scale)
+    G = 3
+    prompts = np.stack([S.make_prompt(70 + g, 32, shape.vocab, shape.mask_id) for g in range(G)])
+    plan = S.make_plan_vocab(5, 400, shape.vocab, shape.mask_id)
+    bitmap = dev(S.plan_bitmap(plan, shape.vocab).view(np.int32), torch.int32)
+    st, ref = B.State(G, cfg), B.State(G, cfg)
+    ctx.state_init(st, dev(prompts, torch.int32))
+    ctx.state_init(ref, dev(prompts, torch.int32))
+    n_seq, rounds = G, 0
+    while n_seq > 0:
+        words = ctx.round_sync(st, bitmap, n_seq)
+        ctx.round(ref, bitmap, n_seq)
+        torch.cuda.synchronize()
+        rounds += 1
+        assert torch.equal(st.canvas, ref.canvas)
+        for g in range(G):
+            assert words[g] == (int(ref.done[g]), int(ref.n_drafts[g]), *ref.n_commit[g].cpu().tolist())
+        n_seq = sum(0 if w[0] else 1 + w[1] for w in words)
+        assert rounds <= 40
+    assert int(ref.done.sum()) == G
+
+
+def test_forward_driven_decode_accepts_planning_and_ar_drafts():
+    """A model with self-consistent predictions (S.make_consistent_weights): through real forwards a planning
+    draft passes Eq. (at) and wins Filter 2, and AR drafts pass the acceptance set of Sec. 4.3; every round of
+    the decode, accepted drafts included, equals the oracle's."""
+    shape = S.TINY
+    w = S.make_consistent_weights(shape, seed=0, mix=20.0)
+    ctx = make_context(shape, to_device(w), max_seqs=4, max_T=96, max_rows=64)
+    cache = {}
+
+    def fwd(canvas):
+        key = bytes(np.asarray(canvas, np.int32))
+        if key not in cache:
+            cache[key] = O.forward(canvas, w, oracle_model_cfg(shape))
+        return cache[key]
+
+    cfg = B.DecodeCfg(block_len=32, prompt_len=32, gen_len=64, K=3, tau_high=0.5, tau_plan_lo=0.05, tau_plan_hi=0.4,
+                      tau_ar_lo=0.01, logit_scale=24.0)
+    plan = S.prior_plan_vocab(w, 256, shape.mask_id)
+    ocfg = oracle_decode_cfg(cfg)
+    for seed in range(1, 20):
+        prompt = S.make_prompt(seed, cfg.prompt_len, shape.vocab, shape.mask_id)
+        ref = O.decode(prompt, fwd, ocfg, cfg.logit_scale, shape.mask_id, plan)
+        acc = {1: 0, 2: 0}
+        for r in ref.rounds:
+            if r.accept:
+                acc[r.route] += sum(r.accept)
+        if ref.margin >= MARGIN and acc[1] > 0 and acc[2] > 0 and ref.n_plan > 0 and ref.n_ar > 0:
+            break
+    else:
+        pytest.fail("no prompt on which both a planning draft and an AR draft are accepted")
+    st, rounds = step_and_compare(shape, ctx, fwd, cfg, [prompt], plan, compact=True)
+    assert rounds == ref.nfe and np.array_equal(st.canvas[0, 0].cpu().numpy(), ref.tokens)
+    bitmap = dev(S.plan_bitmap(plan, shape.vocab).view(np.int32), torch.int32)
+    out, stats = ctx.decode(B.State(1, cfg), dev(prompt[None], torch.int32), bitmap)
+    assert np.array_equal(out[0].cpu().numpy(), ref.tokens)
+    assert (stats.n_base, stats.n_plan, stats.n_ar) == (ref.n_base, ref.n_plan, ref.n_ar)
+    assert stats.n_plan > 0 and stats.n_ar > 0 and stats.drafts_accepted > 0

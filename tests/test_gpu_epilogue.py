@@ -96,11 +96,16 @@ def draft_consistent_logits(rng, G, K, R, V, mask_id, boost_hi, jitter):
 
 
 def run_two_rounds(seed, G, K, bl, gen_len, V, dtype, routes=3, tau_high=0.9, boost_hi=18.0,
-                   plan_n=None, jitter=0.4, prompt_len=4, band=(0.2, 0.65), n_sparse=0, rounds=3):
+                   plan_n=None, jitter=0.4, prompt_len=4, band=(0.2, 0.65), n_sparse=0, rounds=3,
+                   persistent=False, round_jitter=0.15, tau_ar=0.1):
+    """persistent: every round scores the SAME boosted table plus fresh small noise (a model whose
+    predictions persist from round to round), so that AR fills proposed in one round can still be the
+    arg-max in the next (accepted) and the impact set of a round holds only rows that newly crossed
+    tau_high (sometimes none: rejected).  Otherwise every round draws a fresh table."""
     mask_id = V - 1
     cfg = B.DecodeCfg(block_len=bl, prompt_len=prompt_len, gen_len=gen_len, K=K, routes=routes,
-                      tau_high=tau_high, tau_plan_lo=band[0], tau_plan_hi=band[1], logit_scale=1.0,
-                      n_sparse=n_sparse)
+                      tau_high=tau_high, tau_plan_lo=band[0], tau_plan_hi=band[1], tau_ar_lo=tau_ar,
+                      logit_scale=1.0, n_sparse=n_sparse)
     ocfg = oracle_decode_cfg(cfg)
     R = cfg.R
     rng = np.random.default_rng(seed)
@@ -114,8 +119,15 @@ def run_two_rounds(seed, G, K, bl, gen_len, V, dtype, routes=3, tau_high=0.9, bo
     ost = [O.initial_state(prompts[g], ocfg, mask_id) for g in range(G)]
     margin = np.inf
     seen = {"accept": 0, "reject": 0, "plan": 0, "ar": 0, "wide": 0, "wide_accept": 0}
+    table = S.make_boosted_logits(seed + 3, G * R, V, boost_hi, mask_id).reshape(G, 1, R, V) if persistent else None
     for rnd in range(rounds):
-        lg = draft_consistent_logits(rng, G, K, R, V, mask_id, boost_hi, jitter)
+        if persistent:
+            lg = np.repeat(table, 1 + K, axis=1)
+            lg[:, :1] += rng.standard_normal((G, 1, R, V)).astype(np.float32) * round_jitter
+            lg[:, 1:] += rng.standard_normal((G, K, R, V)).astype(np.float32) * jitter
+            lg = S.bf16_round(lg)
+        else:
+            lg = draft_consistent_logits(rng, G, K, R, V, mask_id, boost_hi, jitter)
         B.epilogue(dev(lg, dtype), st, bitmap, V, mask_id)
         torch.cuda.synchronize()
         for g in range(G):
@@ -196,6 +208,24 @@ def test_epilogue_full_vocabulary_rows():
     seed, seen = walk_seeds(600, G=2, K=4, bl=256, gen_len=256, V=126464, dtype=torch.bfloat16,
                             plan_n=512 * 32, prompt_len=0)
     assert seen["plan"] + seen["ar"] > 0
+
+
+@pytest.mark.parametrize("routes,first_seed,kw", [
+    (1, 610, dict(plan_n=126464 // 2, round_jitter=1.0, jitter=1.0)),   # confidences move between rounds: impact sets form
+    (2, 640, dict(tau_ar=1e-4, jitter=0.3))])                            # weak AR fills: some stop being the arg-max
+def test_epilogue_full_vocabulary_both_outcomes_on_each_route(routes, first_seed, kw):
+    """V = 126464, bf16, predictions that persist between rounds: on the planning route and on the AR
+    route drafts are verified at the real vocabulary width, and both outcomes (accepted, rejected) occur."""
+    tot = {"accept": 0, "reject": 0, "plan": 0, "ar": 0}
+    for k in range(6):
+        seed, seen = walk_seeds(first_seed + 5 * k, G=1, K=4, bl=32, gen_len=64, V=126464, dtype=torch.bfloat16,
+                                prompt_len=0, routes=routes, rounds=5, persistent=True, **kw)
+        for key in tot:
+            tot[key] += seen[key]
+        if tot["accept"] > 0 and tot["reject"] > 0:
+            break
+    assert tot["accept"] > 0 and tot["reject"] > 0, tot
+    assert tot["plan" if routes == 1 else "ar"] > 0 and tot["ar" if routes == 1 else "plan"] == 0, tot
 
 
 def test_epilogue_rejects_bad_configuration():
