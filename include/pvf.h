@@ -272,6 +272,15 @@ pvf_status pvf_plan_vocab_select(void *stream, const uint32_t *cal_n, const uint
 pvf_status pvf_gemm(void *stream, int32_t dtype, const void *A, const void *W, void *C,
                     const void *residual, int32_t M, int32_t N, int32_t K);
 
+/* The same products as a context launches them: with the context's workspace, launches of up to 640 rows
+ * (the window forward of a K/V-cached round, the full forward of one short canvas) split K over several
+ * workgroups per tile and add the float32 partial tiles in split order.  Operands in the context's dtype.
+ * Launches of one context must not overlap (they share that workspace). */
+pvf_status pvf_ctx_gemm(pvf_ctx *ctx, void *stream, const void *A, const void *W, void *C,
+                        const void *residual, int32_t M, int32_t N, int32_t K);
+pvf_status pvf_ctx_gemm_swiglu(pvf_ctx *ctx, void *stream, const void *A, const void *W, void *act,
+                               int32_t M, int32_t ff, int32_t K);
+
 /* act[M, ff] = silu(A W_gate^T) * (A W_up^T) with W [2*ff, K] (rows gate | up). */
 pvf_status pvf_gemm_swiglu(void *stream, int32_t dtype, const void *A, const void *W, void *act,
                            int32_t M, int32_t ff, int32_t K);

@@ -29,7 +29,8 @@ EXPORTS = ["pvf_create", "pvf_destroy", "pvf_last_error", "pvf_workspace_bytes",
            "pvf_profile_end", "pvf_forward",
            "pvf_epilogue", "pvf_round", "pvf_state_init", "pvf_decode", "pvf_stage1", "pvf_gemm",
            "pvf_gemm_swiglu", "pvf_rmsnorm", "pvf_rope_attention", "pvf_fill_normal", "pvf_entropy",
-           "pvf_plan_vocab_select", "pvf_qkv_attention", "pvf_rope_attention_noalloc", "pvf_round_sync"]
+           "pvf_plan_vocab_select", "pvf_qkv_attention", "pvf_rope_attention_noalloc", "pvf_round_sync", "pvf_ctx_gemm",
+           "pvf_ctx_gemm_swiglu"]
 
 
 class PvfError(RuntimeError):
@@ -123,6 +124,10 @@ def lib() -> C.CDLL:
                                             C.c_float, C.c_void_p]
         L.pvf_gemm.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
                                C.c_void_p, C.c_int32, C.c_int32, C.c_int32]
+        L.pvf_ctx_gemm.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                   C.c_void_p, C.c_int32, C.c_int32, C.c_int32]
+        L.pvf_ctx_gemm_swiglu.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                          C.c_int32, C.c_int32, C.c_int32]
         L.pvf_gemm_swiglu.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
                                       C.c_int32, C.c_int32, C.c_int32]
         L.pvf_rmsnorm.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
@@ -286,6 +291,26 @@ class Context:
         _check(lib().pvf_profile_end(self.handle, _stream(), C.byref(p)), self.handle)
         return {name: {"ms": p.ms[i], "flops": p.flops[i], "bytes": p.bytes[i], "launches": p.launches[i]}
                 for i, name in enumerate(PROF_CATEGORIES)}
+
+    # ---- GEMMs as the context launches them (weight-streaming kernels for few rows) ----
+    def gemm(self, A: torch.Tensor, W: torch.Tensor, residual: Optional[torch.Tensor] = None,
+             out: Optional[torch.Tensor] = None) -> torch.Tensor:
+        M, K = A.shape
+        N = W.shape[0]
+        assert W.shape[1] == K and A.dtype == self.dtype
+        if out is None:
+            out = torch.empty(M, N, dtype=A.dtype, device=A.device)
+        _check(lib().pvf_ctx_gemm(self.handle, _stream(), _ptr(A), _ptr(W), _ptr(out), _ptr(residual), M, N, K),
+               self.handle)
+        return out
+
+    def gemm_swiglu(self, A: torch.Tensor, W: torch.Tensor, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+        M, K = A.shape
+        ff = W.shape[0] // 2
+        if out is None:
+            out = torch.empty(M, ff, dtype=A.dtype, device=A.device)
+        _check(lib().pvf_ctx_gemm_swiglu(self.handle, _stream(), _ptr(A), _ptr(W), _ptr(out), M, ff, K), self.handle)
+        return out
 
     # ---- the four calls -------------------------------------------------------------
     def forward(self, tokens: torch.Tensor, row_pos: torch.Tensor) -> torch.Tensor:

@@ -147,6 +147,15 @@ enum GemmEpilogue { kEpiStore = 0, kEpiResidual = 1, kEpiSwiglu = 2, kEpiQkvRope
 // C[M,N] = silu(gate) * up.
 pvf_status launch_gemm(pvf_ctx *ctx, hipStream_t s, int dtype, GemmEpilogue epi, const void *A,
                        const void *W, void *C, const void *residual, int M, int N, int K);
+// Pieces of the split-K path for launches of few rows.
+// out[M, N] = epilogue(sum over splits of partial[z][M][Nw]) in split order (store, + residual, SwiGLU of gate | up halves)
+pvf_status launch_splitk_finalize(pvf_ctx *ctx, hipStream_t s, GemmEpilogue epi, const float *partial, int splits,
+                                  int M, int N, void *C, const void *residual);
+// h[m, :] <- h[m, :] + sum over splits of partial[z][m][:] (rounded once), then out[m, :] = RMSNorm(h[m, :]) * gain
+pvf_status launch_reduce_residual_rmsnorm(pvf_ctx *ctx, hipStream_t s, const float *partial, int splits, int M, int d,
+                                          void *h, const void *gain, void *out, float eps);
+bool reduce_residual_rmsnorm_supported(int dtype, int d);
+
 pvf_status launch_fill_normal(pvf_ctx *ctx, hipStream_t s, int dtype, void *dst, int64_t n,
                               uint64_t seed, float mean, float std);
 

@@ -182,6 +182,84 @@ pvf_status launch_rmsnorm(pvf_ctx *ctx, hipStream_t s, int dtype, const void *x,
   return PVF_OK;
 }
 
+// Finishes a split-K projection that writes into the residual stream and norms the result for the next
+// projection, one workgroup per row: h <- bf16(h + sum_z partial[z]) (split order, rounded once), then
+// out = bf16(h * rsqrt(mean(h^2) + eps) * gain) on the rounded values -- what the residual epilogue followed
+// by rmsnorm_bf16_vec_kernel computes, without writing and re-reading h in between.
+template <int MAXV>
+__global__ void __launch_bounds__(256)
+reduce_residual_rmsnorm_kernel(const float *__restrict__ partial, int splits, int M, bf16_t *__restrict__ h,
+                               const bf16_t *__restrict__ gain, bf16_t *__restrict__ out, int d, float eps) {
+  const int64_t m = blockIdx.x;
+  const int nvec = d / 8;
+  uint4 *hr = reinterpret_cast<uint4 *>(h + m * d);
+  const uint4 *gr = reinterpret_cast<const uint4 *>(gain);
+  uint4 *orow = reinterpret_cast<uint4 *>(out + m * d);
+  uint4 v[MAXV];
+  float ss = 0.f;
+#pragma unroll
+  for (int k = 0; k < MAXV; ++k) {
+    const int i = threadIdx.x + k * 256;
+    if (i < nvec) {
+      float a[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) a[e] = 0.f;
+      for (int z = 0; z < splits; ++z) {
+        const float4 *pr = reinterpret_cast<const float4 *>(partial + ((int64_t)z * M + m) * d + (int64_t)i * 8);
+        const float4 p0 = pr[0], p1 = pr[1];
+        a[0] += p0.x; a[1] += p0.y; a[2] += p0.z; a[3] += p0.w; a[4] += p1.x; a[5] += p1.y; a[6] += p1.z; a[7] += p1.w;
+      }
+      const uint4 r4 = hr[i];
+      const uint32_t rw[4] = {r4.x, r4.y, r4.z, r4.w};
+      uint32_t o[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const bf16_t lo = (bf16_t)(a[2 * q] + __uint_as_float(rw[q] << 16));
+        const bf16_t hi = (bf16_t)(a[2 * q + 1] + __uint_as_float(rw[q] & 0xffff0000u));
+        o[q] = (uint32_t)__builtin_bit_cast(uint16_t, lo) | ((uint32_t)__builtin_bit_cast(uint16_t, hi) << 16);
+        const float x = __uint_as_float(o[q] << 16), y = __uint_as_float(o[q] & 0xffff0000u);
+        ss += x * x + y * y;
+      }
+      v[k] = make_uint4(o[0], o[1], o[2], o[3]);
+      hr[i] = v[k];
+    }
+  }
+  __shared__ float s_part[4];
+  ss = wave_sum(ss);
+  if (threadIdx.x % kWave == 0) s_part[threadIdx.x / kWave] = ss;
+  __syncthreads();
+  const float r = rsqrtf((s_part[0] + s_part[1] + s_part[2] + s_part[3]) / (float)d + eps);
+#pragma unroll
+  for (int k = 0; k < MAXV; ++k) {
+    const int i = threadIdx.x + k * 256;
+    if (i < nvec) {
+      const uint4 g4 = gr[i];
+      const uint32_t w[4] = {v[k].x, v[k].y, v[k].z, v[k].w};
+      const uint32_t gw[4] = {g4.x, g4.y, g4.z, g4.w};
+      uint32_t o[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const float a = __uint_as_float(w[q] << 16) * r * __uint_as_float(gw[q] << 16);
+        const float b = __uint_as_float(w[q] & 0xffff0000u) * r * __uint_as_float(gw[q] & 0xffff0000u);
+        const bf16_t ab = (bf16_t)a, bb = (bf16_t)b;
+        o[q] = (uint32_t)__builtin_bit_cast(uint16_t, ab) | ((uint32_t)__builtin_bit_cast(uint16_t, bb) << 16);
+      }
+      orow[i] = make_uint4(o[0], o[1], o[2], o[3]);
+    }
+  }
+}
+
+bool reduce_residual_rmsnorm_supported(int dtype, int d) { return dtype == PVF_BF16 && d % 8 == 0 && d / 8 <= 256 * 2; }
+
+pvf_status launch_reduce_residual_rmsnorm(pvf_ctx *ctx, hipStream_t s, const float *partial, int splits, int M, int d,
+                                          void *h, const void *gain, void *out, float eps) {
+  if (M == 0) return PVF_OK;
+  PVF_REQUIRE(ctx, d % 8 == 0 && d / 8 <= 256 * 2 && splits >= 1, PVF_ESHAPE, "reduce_residual_rmsnorm: d=%d splits=%d", d, splits);
+  reduce_residual_rmsnorm_kernel<2><<<M, 256, 0, s>>>(partial, splits, M, (bf16_t *)h, (const bf16_t *)gain, (bf16_t *)out, d, eps);
+  PVF_LAUNCH_CHECK(ctx, "reduce_residual_rmsnorm");
+  return PVF_OK;
+}
+
 pvf_status launch_gather_rows(pvf_ctx *ctx, hipStream_t s, int dtype, const void *h,
                               const int32_t *row_pos, int S, int T, int R, int d, void *out) {
   const unsigned rows = (unsigned)(S * (int64_t)R);

@@ -662,27 +662,43 @@ bool gemm_mfma_splitk_supported(int dtype, GemmEpilogue epi, int M, int N, int K
   return splits >= 2 || (splits == 1 && epi == kEpiSwiglu && M > 128 && M <= 384);
 }
 
-pvf_status launch_gemm_mfma_splitk(pvf_ctx *ctx, hipStream_t s, GemmEpilogue epi, const void *A, const void *W,
-                                   void *C, const void *residual, int M, int N, int K, float *ws, size_t ws_floats) {
-  const uintptr_t al = (uintptr_t)A | (uintptr_t)W | (uintptr_t)C | (uintptr_t)residual | (uintptr_t)ws;
+// The split-K launch alone: float32 partial tiles ws[split][M][Nw] (Nw = weight rows: 2 N for SwiGLU); *splits_out
+// = number of splits written.
+pvf_status launch_gemm_mfma_splitk_partial(pvf_ctx *ctx, hipStream_t s, const void *A, const void *W, int M, int Nw, int K,
+                                           float *ws, size_t ws_floats, int *splits_out) {
+  const uintptr_t al = (uintptr_t)A | (uintptr_t)W | (uintptr_t)ws;
   PVF_REQUIRE(ctx, (al & 15u) == 0, PVF_EINVAL, "gemm_mfma: operands must be 16-byte aligned");
-  const int Nw = epi == kEpiSwiglu ? 2 * N : N;
   int tile, splits;
   splitk_plan(M, Nw, K, ws_floats, &tile, &splits);
-  PVF_REQUIRE(ctx, splits >= 1 && ws != nullptr, PVF_ESHAPE, "gemm_mfma: no split-K plan for M=%d N=%d K=%d", M, N, K);
+  PVF_REQUIRE(ctx, splits >= 1 && ws != nullptr, PVF_ESHAPE, "gemm_mfma: no split-K plan for M=%d N=%d K=%d", M, Nw, K);
   const SplitK sk{ws, K / 64 / splits};
-  pvf_status st;
-  if (tile == 3) st = run<kEpiPartial, 128, 128, 64, 3, 4, 2>(ctx, s, A, W, nullptr, nullptr, M, Nw, K, RopeArgs{}, sk, splits);
-  else if (tile == 7) st = run<kEpiPartial, 64, 128, 64, 3, 2, 2>(ctx, s, A, W, nullptr, nullptr, M, Nw, K, RopeArgs{}, sk, splits);
-  else if (tile == 8) st = run<kEpiPartial, 192, 128, 64, 3, 2, 4>(ctx, s, A, W, nullptr, nullptr, M, Nw, K, RopeArgs{}, sk, splits);
-  else st = run<kEpiPartial, 320, 128, 64, 2, 4, 2>(ctx, s, A, W, nullptr, nullptr, M, Nw, K, RopeArgs{}, sk, splits);
-  if (st != PVF_OK) return st;
+  *splits_out = splits;
+  if (tile == 3) return run<kEpiPartial, 128, 128, 64, 3, 4, 2>(ctx, s, A, W, nullptr, nullptr, M, Nw, K, RopeArgs{}, sk, splits);
+  if (tile == 7) return run<kEpiPartial, 64, 128, 64, 3, 2, 2>(ctx, s, A, W, nullptr, nullptr, M, Nw, K, RopeArgs{}, sk, splits);
+  if (tile == 8) return run<kEpiPartial, 192, 128, 64, 3, 2, 4>(ctx, s, A, W, nullptr, nullptr, M, Nw, K, RopeArgs{}, sk, splits);
+  return run<kEpiPartial, 320, 128, 64, 2, 4, 2>(ctx, s, A, W, nullptr, nullptr, M, Nw, K, RopeArgs{}, sk, splits);
+}
+
+pvf_status launch_splitk_finalize(pvf_ctx *ctx, hipStream_t s, GemmEpilogue epi, const float *partial, int splits,
+                                  int M, int N, void *C, const void *residual) {
+  const int Nw = epi == kEpiSwiglu ? 2 * N : N;
   const int blocks = (int)(((int64_t)M * (N / 8) + 255) / 256);
-  if (epi == kEpiSwiglu) splitk_finalize_kernel<kEpiSwiglu><<<blocks, 256, 0, s>>>(ws, splits, M, Nw, N, (bf16_t *)C, nullptr);
-  else if (epi == kEpiResidual) splitk_finalize_kernel<kEpiResidual><<<blocks, 256, 0, s>>>(ws, splits, M, Nw, N, (bf16_t *)C, (const bf16_t *)residual);
-  else splitk_finalize_kernel<kEpiStore><<<blocks, 256, 0, s>>>(ws, splits, M, Nw, N, (bf16_t *)C, nullptr);
+  if (blocks == 0) return PVF_OK;
+  if (epi == kEpiSwiglu) splitk_finalize_kernel<kEpiSwiglu><<<blocks, 256, 0, s>>>(partial, splits, M, Nw, N, (bf16_t *)C, nullptr);
+  else if (epi == kEpiResidual) splitk_finalize_kernel<kEpiResidual><<<blocks, 256, 0, s>>>(partial, splits, M, Nw, N, (bf16_t *)C, (const bf16_t *)residual);
+  else splitk_finalize_kernel<kEpiStore><<<blocks, 256, 0, s>>>(partial, splits, M, Nw, N, (bf16_t *)C, nullptr);
   PVF_LAUNCH_CHECK(ctx, "splitk_finalize");
   return PVF_OK;
+}
+
+pvf_status launch_gemm_mfma_splitk(pvf_ctx *ctx, hipStream_t s, GemmEpilogue epi, const void *A, const void *W,
+                                   void *C, const void *residual, int M, int N, int K, float *ws, size_t ws_floats) {
+  const uintptr_t al = (uintptr_t)C | (uintptr_t)residual;
+  PVF_REQUIRE(ctx, (al & 15u) == 0, PVF_EINVAL, "gemm_mfma: operands must be 16-byte aligned");
+  int splits = 0;
+  pvf_status st = launch_gemm_mfma_splitk_partial(ctx, s, A, W, M, epi == kEpiSwiglu ? 2 * N : N, K, ws, ws_floats, &splits);
+  if (st != PVF_OK) return st;
+  return launch_splitk_finalize(ctx, s, epi, ws, splits, M, N, C, residual);
 }
 
 

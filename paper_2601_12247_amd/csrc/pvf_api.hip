@@ -100,6 +100,8 @@ pvf_status launch_rope_vt_rows(pvf_ctx *, hipStream_t, void *, void *, const int
 pvf_status launch_attention_window_mfma(pvf_ctx *, hipStream_t, const void *, const void *, const void *, const void *,
                                         int64_t, const int32_t *, const int32_t *, int, int, int, int, int, int, int, void *);
 
+pvf_status launch_gemm_mfma_splitk_partial(pvf_ctx *, hipStream_t, const void *, const void *, int, int, int, float *, size_t, int *);
+
 static bool force_simple() {
   static const bool v = [] { const char *e = getenv("PVF_FORCE_SIMPLE"); return e && e[0] == '1'; }();
   return v;
@@ -355,9 +357,23 @@ static pvf_status forward_window_impl(pvf_ctx *c, hipStream_t s, const pvf_decod
   } while (0)
   RUN(launch_embed_rows(c, s, dt, c->w.embed, state.canvas, seq_slot, row_pos, M, R, T, d, m.vocab, c->h));
   const int64_t gstride = (int64_t)m.n_layers * T * d;
+  // h += A W^T, then out = RMSNorm(h) * gain for the next projection.  Where the projection splits K (few rows)
+  // one kernel adds the partial tiles and the residual and norms the row; otherwise the residual epilogue and the
+  // norm run as two launches.
+  const bool fuse_norm = !force_simple() && c->splitk_ws && reduce_residual_rmsnorm_supported(dt, d);
+  auto project_residual_norm = [&](const void *A, const void *W, int Kk, const void *gain, void *out) -> pvf_status {
+    if (fuse_norm && gemm_mfma_splitk_supported(dt, kEpiResidual, M, d, Kk, c->splitk_floats)) {
+      int splits = 0;
+      ProfScope ps(c, s, PVF_PROF_GEMM, 2.0 * M * (double)d * Kk, (double)c->esize * ((double)M * Kk + (double)d * Kk + 2.0 * M * d));
+      RUN(launch_gemm_mfma_splitk_partial(c, s, A, W, M, d, Kk, c->splitk_ws, c->splitk_floats, &splits));
+      return launch_reduce_residual_rmsnorm(c, s, c->splitk_ws, splits, M, d, c->h, gain, out, m.rms_eps);
+    }
+    RUN_GEMM(kEpiResidual, A, W, c->h, c->h, M, d, Kk);
+    return launch_rmsnorm(c, s, dt, c->h, gain, out, M, d, m.rms_eps);
+  };
+  RUN(launch_rmsnorm(c, s, dt, c->h, c->attn_norm[0], c->xn, M, d, m.rms_eps));
   for (int l = 0; l < m.n_layers; ++l) {
     const int64_t layer_off = (int64_t)l * T * d * c->esize;
-    RUN(launch_rmsnorm(c, s, dt, c->h, c->attn_norm[l], c->xn, M, d, m.rms_eps));
     RUN_GEMM(kEpiStore, c->xn, c->wqkv[l], c->qkv, nullptr, M, 3 * d, d);
     {
       ProfScope ps(c, s, PVF_PROF_ATTENTION, 4.0 * S * (double)R * T * d, 0.0);
@@ -372,12 +388,11 @@ static pvf_status forward_window_impl(pvf_ctx *c, hipStream_t s, const pvf_decod
                                     gstride, cfg, state, seq_slot, S, H, dh, c->att));
       }
     }
-    RUN_GEMM(kEpiResidual, c->att, c->wo[l], c->h, c->h, M, d, d);
-    RUN(launch_rmsnorm(c, s, dt, c->h, c->ffn_norm[l], c->xn, M, d, m.rms_eps));
+    RUN(project_residual_norm(c->att, c->wo[l], d, c->ffn_norm[l], c->xn));
     RUN_GEMM(kEpiSwiglu, c->xn, c->w_gate_up[l], c->act, nullptr, M, ff, d);
-    RUN_GEMM(kEpiResidual, c->act, c->w_down[l], c->h, c->h, M, d, ff);
+    const bool last = l + 1 == m.n_layers;
+    RUN(project_residual_norm(c->act, c->w_down[l], ff, last ? c->w.final_norm : c->attn_norm[l + 1], last ? c->hrows : c->xn));
   }
-  RUN(launch_rmsnorm(c, s, dt, c->h, c->w.final_norm, c->hrows, M, d, m.rms_eps));
   RUN_GEMM(kEpiStore, c->hrows, c->w.out_head, logits, nullptr, M, m.vocab, d);
 #undef RUN_GEMM
 #undef RUN
@@ -729,6 +744,20 @@ extern "C" pvf_status pvf_gemm(void *stream, int32_t dtype, const void *A, const
   if (check_dtype(dtype) != PVF_OK) return PVF_EINVAL;
   PVF_REQUIRE(nullptr, A && W && C && M >= 0 && N >= 0 && K > 0, PVF_EINVAL, "pvf_gemm: bad argument");
   return launch_gemm(nullptr, (hipStream_t)stream, dtype, residual ? kEpiResidual : kEpiStore, A, W, C, residual, M, N, K);
+}
+
+extern "C" pvf_status pvf_ctx_gemm(pvf_ctx *ctx, void *stream, const void *A, const void *W, void *C,
+                                   const void *residual, int32_t M, int32_t N, int32_t K) {
+  PVF_REQUIRE(nullptr, ctx != nullptr, PVF_EINVAL, "pvf_ctx_gemm: ctx is NULL");
+  PVF_REQUIRE(ctx, A && W && C && M >= 0 && N >= 0 && K > 0, PVF_EINVAL, "pvf_ctx_gemm: bad argument");
+  return launch_gemm(ctx, (hipStream_t)stream, ctx->model.dtype, residual ? kEpiResidual : kEpiStore, A, W, C, residual, M, N, K);
+}
+
+extern "C" pvf_status pvf_ctx_gemm_swiglu(pvf_ctx *ctx, void *stream, const void *A, const void *W, void *act,
+                                          int32_t M, int32_t ff, int32_t K) {
+  PVF_REQUIRE(nullptr, ctx != nullptr, PVF_EINVAL, "pvf_ctx_gemm_swiglu: ctx is NULL");
+  PVF_REQUIRE(ctx, A && W && act && M >= 0 && ff >= 0 && K > 0, PVF_EINVAL, "pvf_ctx_gemm_swiglu: bad argument");
+  return launch_gemm(ctx, (hipStream_t)stream, ctx->model.dtype, kEpiSwiglu, A, W, act, nullptr, M, ff, K);
 }
 
 extern "C" pvf_status pvf_gemm_swiglu(void *stream, int32_t dtype, const void *A, const void *W,
