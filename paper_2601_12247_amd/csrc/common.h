@@ -133,9 +133,12 @@ pvf_status launch_copy_out(pvf_ctx *ctx, hipStream_t s, int G, int K, int T,
                            const int32_t *canvas, int32_t *out_tokens);
 
 // forward building blocks
+// ss (bf16 only, may be NULL): ss[m] = sum of squares of row m
 pvf_status launch_embed(pvf_ctx *ctx, hipStream_t s, int dtype, const void *embed,
                         const int32_t *tokens, const int32_t *seq_slot, int S, int T, int d,
-                        int vocab, void *h);
+                        int vocab, void *h, float *ss = nullptr);
+// out[n, k] = bf16(w[n, k] * gain[k])
+pvf_status launch_fold_gain(pvf_ctx *ctx, hipStream_t s, const void *w, const void *gain, void *out, int64_t n, int k);
 pvf_status launch_rmsnorm(pvf_ctx *ctx, hipStream_t s, int dtype, const void *x,
                           const void *gain, void *out, int M, int d, float eps);
 pvf_status launch_gather_rows(pvf_ctx *ctx, hipStream_t s, int dtype, const void *h,
@@ -143,6 +146,17 @@ pvf_status launch_gather_rows(pvf_ctx *ctx, hipStream_t s, int dtype, const void
 pvf_status launch_rope(pvf_ctx *ctx, hipStream_t s, int dtype, void *qkv, int M, int T,
                        int n_heads, int d_head, const float2 *cos_sin);
 enum GemmEpilogue { kEpiStore = 0, kEpiResidual = 1, kEpiSwiglu = 2, kEpiQkvRope = 3, kEpiPartial = 4 };
+// RMSNorm folded into the projections around it (bf16 MFMA GEMMs of launches above the split-K range):
+// the projection that writes the residual stream also writes, per output tile column `slot`, the sum of
+// squares of each row's (rounded) values, ss[slot * ld + m]; the projection that reads the stream takes h
+// itself as its operand, with the gain folded into its weights, and multiplies row m of its accumulators by
+// rsqrt(sum over slots of ss / d + eps) in its epilogue.
+struct NormArgs {
+  float *ss_out = nullptr;        // kEpiResidual: where the row sums of squares of this launch go
+  const float *ss_in = nullptr;   // kEpiSwiglu / kEpiQkvRope: row sums of squares of the operand rows
+  int32_t n_slots_in = 0, ld = 0; // slots to add up; rows per slot
+  float inv_d = 0.f, eps = 0.f;
+};
 // C[M,N] = A[M,K] W[N,K]^T; kEpiResidual adds residual[M,N]; kEpiSwiglu: W is [2N,K] (gate|up),
 // C[M,N] = silu(gate) * up.
 pvf_status launch_gemm(pvf_ctx *ctx, hipStream_t s, int dtype, GemmEpilogue epi, const void *A,

@@ -13,7 +13,8 @@ template <typename T> struct Pack { static constexpr int N = 16 / sizeof(T); };
 template <typename T>
 __global__ void __launch_bounds__(256)
 embed_kernel(const T *__restrict__ embed, const int32_t *__restrict__ tokens,
-             const int32_t *__restrict__ seq_slot, int T_len, int d, int vocab, T *__restrict__ h) {
+             const int32_t *__restrict__ seq_slot, int T_len, int d, int vocab, T *__restrict__ h,
+             float *__restrict__ ss_out) {
   const int64_t m = blockIdx.x;
   const int s = (int)(m / T_len), t = (int)(m % T_len);
   const int slot = seq_slot ? seq_slot[s] : s;
@@ -22,7 +23,43 @@ embed_kernel(const T *__restrict__ embed, const int32_t *__restrict__ tokens,
   constexpr int N = Pack<T>::N;
   const uint4 *src = reinterpret_cast<const uint4 *>(embed + (int64_t)id * d);
   uint4 *dst = reinterpret_cast<uint4 *>(h + m * d);
-  for (int i = threadIdx.x; i < d / N; i += blockDim.x) dst[i] = src[i];
+  float ss = 0.f;
+  for (int i = threadIdx.x; i < d / N; i += blockDim.x) {
+    const uint4 v = src[i];
+    dst[i] = v;
+    if (sizeof(T) == 2 && ss_out) {                     // row sum of squares for the norm folded into the first projection
+      const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const float a = __uint_as_float(w[q] << 16), b = __uint_as_float(w[q] & 0xffff0000u);
+        ss += a * a + b * b;
+      }
+    }
+  }
+  if (sizeof(T) == 2 && ss_out) {                       // uniform branch
+    __shared__ float s_part[4];
+    ss = wave_sum(ss);
+    if (threadIdx.x % kWave == 0) s_part[threadIdx.x / kWave] = ss;
+    __syncthreads();
+    if (threadIdx.x == 0) ss_out[m] = s_part[0] + s_part[1] + s_part[2] + s_part[3];
+  }
+}
+
+// out[n][k] = bf16(w[n][k] * gain[k]); one thread = 8 consecutive k
+__global__ void __launch_bounds__(256)
+fold_gain_kernel(const bf16_t *__restrict__ w, const bf16_t *__restrict__ gain, bf16_t *__restrict__ out, int64_t nvec, int kvec) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= nvec) return;
+  const uint4 a = reinterpret_cast<const uint4 *>(w)[i], g = reinterpret_cast<const uint4 *>(gain)[i % kvec];
+  const uint32_t aw[4] = {a.x, a.y, a.z, a.w}, gw[4] = {g.x, g.y, g.z, g.w};
+  uint32_t o[4];
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    const bf16_t lo = (bf16_t)(__uint_as_float(aw[q] << 16) * __uint_as_float(gw[q] << 16));
+    const bf16_t hi = (bf16_t)(__uint_as_float(aw[q] & 0xffff0000u) * __uint_as_float(gw[q] & 0xffff0000u));
+    o[q] = (uint32_t)__builtin_bit_cast(uint16_t, lo) | ((uint32_t)__builtin_bit_cast(uint16_t, hi) << 16);
+  }
+  reinterpret_cast<uint4 *>(out)[i] = make_uint4(o[0], o[1], o[2], o[3]);
 }
 
 // ---- RMSNorm: out = x * rsqrt(mean(x^2) + eps) * gain, one row per block ---------------
@@ -157,13 +194,22 @@ __global__ void fill_normal_kernel(T *__restrict__ dst, int64_t n, uint64_t seed
 
 pvf_status launch_embed(pvf_ctx *ctx, hipStream_t s, int dtype, const void *embed,
                         const int32_t *tokens, const int32_t *seq_slot, int S, int T, int d,
-                        int vocab, void *h) {
+                        int vocab, void *h, float *ss) {
   const unsigned M = (unsigned)(S * (int64_t)T);
+  if (M == 0) return PVF_OK;
   if (dtype == PVF_BF16)
-    embed_kernel<bf16_t><<<M, 256, 0, s>>>((const bf16_t *)embed, tokens, seq_slot, T, d, vocab, (bf16_t *)h);
+    embed_kernel<bf16_t><<<M, 256, 0, s>>>((const bf16_t *)embed, tokens, seq_slot, T, d, vocab, (bf16_t *)h, ss);
   else
-    embed_kernel<float><<<M, 256, 0, s>>>((const float *)embed, tokens, seq_slot, T, d, vocab, (float *)h);
+    embed_kernel<float><<<M, 256, 0, s>>>((const float *)embed, tokens, seq_slot, T, d, vocab, (float *)h, nullptr);
   PVF_LAUNCH_CHECK(ctx, "embed");
+  return PVF_OK;
+}
+
+pvf_status launch_fold_gain(pvf_ctx *ctx, hipStream_t s, const void *w, const void *gain, void *out, int64_t n, int k) {
+  PVF_REQUIRE(ctx, k % 8 == 0 && n > 0, PVF_ESHAPE, "fold_gain: n=%lld k=%d", (long long)n, k);
+  const int64_t nvec = n * (k / 8);
+  fold_gain_kernel<<<(unsigned)((nvec + 255) / 256), 256, 0, s>>>((const bf16_t *)w, (const bf16_t *)gain, (bf16_t *)out, nvec, k / 8);
+  PVF_LAUNCH_CHECK(ctx, "fold_gain");
   return PVF_OK;
 }
 

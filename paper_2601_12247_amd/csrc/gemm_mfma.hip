@@ -106,7 +106,7 @@ __attribute__((amdgpu_waves_per_eu(waves_per_simd(kStages * (BM + BN) * BK * 2, 
                                    waves_per_simd(kStages * (BM + BN) * BK * 2, WM * WN))))
 gemm_bf16_mfma_kernel(const bf16_t *__restrict__ A, const bf16_t *__restrict__ W,
                       bf16_t *__restrict__ C, const bf16_t *__restrict__ Res, int M, int N_out,
-                      int K, int tiles_m, int tiles_n, int group_m, RopeArgs ra, SplitK sk) {
+                      int K, int tiles_m, int tiles_n, int group_m, RopeArgs ra, SplitK sk, NormArgs na) {
   constexpr int kThreads = 64 * WM * WN;
   constexpr int MT = (BM / WM + 31) / 32;                  // 32-row passes of the epilogue (the last one may have 16 rows)
   constexpr int MT16 = BM / (16 * WM), NT16 = BN / (16 * WN);   // 16x16 MFMA tiles per wave in each direction
@@ -197,6 +197,23 @@ gemm_bf16_mfma_kernel(const bf16_t *__restrict__ A, const bf16_t *__restrict__ W
 #pragma unroll
       for (int i = 0; i < kLoadsPerStage; ++i) issue_one(s, i);
     }
+
+  // Folded RMSNorm on the operand side: thread t < BM adds up the sums of squares of operand row m0 + t now,
+  // while the first stages are in flight (8 loads at a time, slot order), and keeps 1 / rms for the epilogue.
+  static_assert(BM <= kThreads, "one thread per tile row");
+  float my_rnorm = 1.f;
+  if ((EPI == kEpiSwiglu || EPI == kEpiQkvRope) && na.ss_in != nullptr && tid < BM) {
+    const float *src = na.ss_in + min(m0 + tid, M - 1);
+    float t = 0.f;
+    for (int s0 = 0; s0 < na.n_slots_in; s0 += 8) {
+      float v[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) v[j] = s0 + j < na.n_slots_in ? src[(int64_t)(s0 + j) * na.ld] : 0.f;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) t += v[j];
+    }
+    my_rnorm = rsqrtf(t * na.inv_d + na.eps);
+  }
 
   // Waits until at most n whole stages of this wave's direct loads are still in flight.
   auto wait_stages = [&](int n) {
@@ -324,12 +341,25 @@ gemm_bf16_mfma_kernel(const bf16_t *__restrict__ A, const bf16_t *__restrict__ W
       }
   }
   __syncthreads();                                                   // every wave is done with the ring
+  // Folded RMSNorm: kNormOff bytes into the (free) ring lie above every staging area.  A reading projection
+  // puts 1 / rms of its BM operand rows there; a writing one collects the row sums of squares of its output.
+  // (The small tiles of the few-row launches have no room for it and never take part.)
+  constexpr int kNormOff = 80 * 1024;
+  constexpr bool kNormRoom = kNormOff + WN * BM * 4 <= kStages * kStage;
+  float *norm_x = reinterpret_cast<float *>(lds + kNormOff);
+  const bool norm_in = kNormRoom && (EPI == kEpiSwiglu || EPI == kEpiQkvRope) && na.ss_in != nullptr;     // uniform
+  const bool norm_out = kNormRoom && EPI == kEpiResidual && na.ss_out != nullptr;                         // uniform
+  if (norm_in) {
+    if (tid < BM) norm_x[tid] = my_rnorm;
+    __syncthreads();
+  }
   const int rope_third = EPI == kEpiQkvRope ? (tile_n * BN) / (N_out / 3) : 2;   // 0 = q, 1 = k, 2 = v (uniform per workgroup)
   // v third of the QKV projection: a wave keeps two passes (64 keys) in its staging area, so that the
   // key-contiguous copy is written in whole 128-byte lines; columns are XOR-swizzled by the 16-key block
   // of the row, which makes the transposing 2-byte reads free of bank conflicts.
   constexpr int kVPasses = (EPI == kEpiQkvRope && WTM % 64 == 0) ? 2 : 1;
   static_assert(WM * WN * kVPasses * 32 * kStride <= kStages * kStage, "v staging area exceeds the LDS ring");
+  static_assert(!kNormRoom || WM * WN * kVPasses * 32 * kStride <= kNormOff, "staging area reaches into the norm exchange area");
   const bool v_tile = EPI == kEpiQkvRope && rope_third == 2;
   unsigned char *my = lds + wave * ((v_tile ? kVPasses : 1) * 32 * kStride);
   // rotary epilogue: cos / sin of the lane's rows (2 halves of 16) and columns (2 sub-tiles x 4 pairs) of a
@@ -359,6 +389,13 @@ gemm_bf16_mfma_kernel(const bf16_t *__restrict__ A, const bf16_t *__restrict__ W
       unsigned char *wrow = my + (vp * 32 + h * 16 + fr) * kStride;
       const int xs = v_tile ? (2 * vp + h) << 3 : 0;                    // column swizzle of this 16-row block
       const int m16 = 2 * mt + h;
+      if (norm_in) {                                                     // row m16 * 16 + fr of the wave tile
+        const float rs = norm_x[wm * WTM + m16 * 16 + fr];
+#pragma unroll
+        for (int nt = 0; nt < NT16; ++nt)
+#pragma unroll
+          for (int e = 0; e < 4; ++e) acc[nt][m16][e] *= rs;
+      }
       if (EPI == kEpiQkvRope && rope_third < 2) {
         // a = column i of the head (sub-tile nt), b = column i + 64 (sub-tile nt + 2), both rounded to bf16 first
         // (the values a separate rotary pass would read): i <- a cos - b sin, i + 64 <- b cos + a sin
@@ -485,13 +522,35 @@ gemm_bf16_mfma_kernel(const bf16_t *__restrict__ A, const bf16_t *__restrict__ W
         out = *reinterpret_cast<const uint4 *>(my + r * kStride + rd_col * 2);
       }
       if (m < M) *reinterpret_cast<uint4 *>(C + o) = out;
+      if (norm_out) {                                                    // sum of squares of the row's rounded values
+        const uint32_t ow[4] = {out.x, out.y, out.z, out.w};
+        float q = 0.f;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const float a = __uint_as_float(ow[e] << 16), b = __uint_as_float(ow[e] & 0xffff0000u);
+          q += a * a + b * b;
+        }
+#pragma unroll
+        for (int off = 1; off < LPR; off <<= 1) q += __shfl_xor(q, off, 64);   // the LPR lanes that share the row
+        if (rd_col == 0) norm_x[wn * BM + wm * WTM + mt * 32 + r] = q;
+      }
+    }
+  }
+  if (norm_out) {                                                        // add the WN column parts in a fixed order
+    __syncthreads();
+    for (int row = tid; row < BM; row += kThreads) {
+      float t = 0.f;
+#pragma unroll
+      for (int w = 0; w < WN; ++w) t += norm_x[w * BM + row];
+      if (m0 + row < M) na.ss_out[(int64_t)tile_n * na.ld + m0 + row] = t;
     }
   }
 }
 
 template <int EPI, int BM, int BN, int BK, int ST, int WM, int WN>
 pvf_status run(pvf_ctx *ctx, hipStream_t s, const void *A, const void *W, void *C, const void *Res,
-               int M, int N_out, int K, const RopeArgs &ra, const SplitK &sk = SplitK{nullptr, 0}, int splits = 1) {
+               int M, int N_out, int K, const RopeArgs &ra, const SplitK &sk = SplitK{nullptr, 0}, int splits = 1,
+               const NormArgs &na = NormArgs{}) {
   constexpr int kLdsBytes = ST * (BM + BN) * BK * 2;
   static_assert(kLdsBytes <= 160 * 1024, "LDS ring exceeds the 160 KB of a CU");
   // once per kernel instance; a function-local static is initialised exactly once even with concurrent callers
@@ -510,7 +569,7 @@ pvf_status run(pvf_ctx *ctx, hipStream_t s, const void *A, const void *W, void *
   const int n_bands = (tiles_m + kBand - 1) / kBand;
   const int group_m = (tiles_m + n_bands - 1) / n_bands;
   gemm_bf16_mfma_kernel<EPI, BM, BN, BK, ST, WM, WN><<<dim3(grid, splits), 64 * WM * WN, kLdsBytes, s>>>(
-      (const bf16_t *)A, (const bf16_t *)W, (bf16_t *)C, (const bf16_t *)Res, M, N_out, K, tiles_m, tiles_n, group_m, ra, sk);
+      (const bf16_t *)A, (const bf16_t *)W, (bf16_t *)C, (const bf16_t *)Res, M, N_out, K, tiles_m, tiles_n, group_m, ra, sk, na);
   PVF_LAUNCH_CHECK(ctx, "gemm_mfma");
   return PVF_OK;
 }
@@ -534,20 +593,20 @@ constexpr TileCfg kCfg[kNumCfg] = {
 
 template <int EPI>
 pvf_status run_cfg(pvf_ctx *ctx, hipStream_t s, int cfg, const void *A, const void *W, void *C,
-                   const void *Res, int M, int N, int K, const RopeArgs &ra = RopeArgs{}) {
+                   const void *Res, int M, int N, int K, const RopeArgs &ra = RopeArgs{}, const NormArgs &na = NormArgs{}) {
   constexpr bool kPlain = EPI != kEpiSwiglu && EPI != kEpiQkvRope;
   switch (cfg) {
-    case 0: return run<EPI, 256, 256, 64, 2, 2, 4>(ctx, s, A, W, C, Res, M, N, K, ra);
-    case 1: return run<EPI, 128, 256, 64, 3, 2, 4>(ctx, s, A, W, C, Res, M, N, K, ra);
-    case 2: return run<EPI, 256, 128, 64, 3, 4, 2>(ctx, s, A, W, C, Res, M, N, K, ra);
-    case 4: return run<EPI, 192, 256, 64, 2, 2, 4>(ctx, s, A, W, C, Res, M, N, K, ra);
-    case 5: if constexpr (kPlain) return run<EPI, 320, 128, 64, 2, 4, 2>(ctx, s, A, W, C, Res, M, N, K, ra); break;
-    case 6: if constexpr (kPlain) return run<EPI, 64, 64, 64, 5, 2, 2>(ctx, s, A, W, C, Res, M, N, K, ra); break;
-    case 7: return run<EPI, 64, 128, 64, 3, 2, 2>(ctx, s, A, W, C, Res, M, N, K, ra);
-    case 8: if constexpr (kPlain) return run<EPI, 192, 128, 64, 3, 2, 4>(ctx, s, A, W, C, Res, M, N, K, ra); break;
+    case 0: return run<EPI, 256, 256, 64, 2, 2, 4>(ctx, s, A, W, C, Res, M, N, K, ra, SplitK{nullptr, 0}, 1, na);
+    case 1: return run<EPI, 128, 256, 64, 3, 2, 4>(ctx, s, A, W, C, Res, M, N, K, ra, SplitK{nullptr, 0}, 1, na);
+    case 2: return run<EPI, 256, 128, 64, 3, 4, 2>(ctx, s, A, W, C, Res, M, N, K, ra, SplitK{nullptr, 0}, 1, na);
+    case 4: return run<EPI, 192, 256, 64, 2, 2, 4>(ctx, s, A, W, C, Res, M, N, K, ra, SplitK{nullptr, 0}, 1, na);
+    case 5: if constexpr (kPlain) return run<EPI, 320, 128, 64, 2, 4, 2>(ctx, s, A, W, C, Res, M, N, K, ra, SplitK{nullptr, 0}, 1, na); break;
+    case 6: if constexpr (kPlain) return run<EPI, 64, 64, 64, 5, 2, 2>(ctx, s, A, W, C, Res, M, N, K, ra, SplitK{nullptr, 0}, 1, na); break;
+    case 7: return run<EPI, 64, 128, 64, 3, 2, 2>(ctx, s, A, W, C, Res, M, N, K, ra, SplitK{nullptr, 0}, 1, na);
+    case 8: if constexpr (kPlain) return run<EPI, 192, 128, 64, 3, 2, 4>(ctx, s, A, W, C, Res, M, N, K, ra, SplitK{nullptr, 0}, 1, na); break;
     default: break;
   }
-  return run<EPI, 128, 128, 64, 3, 4, 2>(ctx, s, A, W, C, Res, M, N, K, ra);
+  return run<EPI, 128, 128, 64, 3, 4, 2>(ctx, s, A, W, C, Res, M, N, K, ra, SplitK{nullptr, 0}, 1, na);
 }
 
 // Tile shape: the one with the least estimated time = rounds of workgroups over the 256 CUs
@@ -647,6 +706,7 @@ void splitk_plan(int M, int Nw, int K, size_t ws_floats, int *tile, int *splits)
 }  // namespace
 
 bool gemm_mfma_supported(int dtype, GemmEpilogue epi, int M, int N, int K);
+bool gemm_mfma_norm_capable(int cfg);
 
 // Few rows (window forward of the K/V-cached rounds, full forward of one short canvas): tiles as tall as
 // the launch up to 384 rows, so that every weight row goes from L2 to a CU once, and K split over 2-8
@@ -711,14 +771,16 @@ bool gemm_mfma_qkv_rope_supported(int dtype, int M, int N, int K, int T, int H) 
 }
 
 pvf_status launch_gemm_mfma_qkv_rope(pvf_ctx *ctx, hipStream_t s, const void *A, const void *W, void *qkv,
-                                     void *vt, const float2 *cos_sin, int M, int N, int K, int T, int H, bool store_v) {
+                                     void *vt, const float2 *cos_sin, int M, int N, int K, int T, int H, bool store_v,
+                                     const NormArgs *na) {
   const uintptr_t al = (uintptr_t)A | (uintptr_t)W | (uintptr_t)qkv | (uintptr_t)vt;
   PVF_REQUIRE(ctx, (al & 15u) == 0, PVF_EINVAL, "gemm_mfma: operands must be 16-byte aligned");
   const int cfg = pick_config(kEpiQkvRope, M, N, K);
   PVF_REQUIRE(ctx, cfg >= 0, PVF_ESHAPE, "gemm_mfma: no tile shape with a rotary epilogue for N=%d", N);
   RopeArgs ra;
   ra.cos_sin = cos_sin; ra.vt = (bf16_t *)vt; ra.T = T; ra.H = H; ra.store_v = store_v;
-  return run_cfg<kEpiQkvRope>(ctx, s, cfg, A, W, qkv, nullptr, M, N, K, ra);
+  PVF_REQUIRE(ctx, !na || !na->ss_in || gemm_mfma_norm_capable(cfg), PVF_ESHAPE, "gemm_mfma: tile shape %d cannot fold the norm", cfg);
+  return run_cfg<kEpiQkvRope>(ctx, s, cfg, A, W, qkv, nullptr, M, N, K, ra, na ? *na : NormArgs{});
 }
 
 bool gemm_mfma_supported(int dtype, GemmEpilogue epi, int M, int N, int K) {
@@ -728,16 +790,30 @@ bool gemm_mfma_supported(int dtype, GemmEpilogue epi, int M, int N, int K) {
   return N % (epi == kEpiSwiglu ? 64 : 128) == 0;
 }
 
+// Tile shapes with room for the folded-norm exchange (every 8-wave shape).
+bool gemm_mfma_norm_capable(int cfg) { return cfg >= 0 && cfg != 6 && cfg != 7; }
+
+// Output tile columns (= slots of row sums of squares a kEpiResidual launch writes); 0: no folded norm for this launch.
+int gemm_mfma_norm_slots(GemmEpilogue epi, int M, int N, int K) {
+  if (!gemm_mfma_supported(PVF_BF16, epi, M, N, K)) return 0;
+  const int cfg = pick_config(epi, M, N, K);
+  if (!gemm_mfma_norm_capable(cfg)) return 0;
+  const int c = cfg == 3 || cfg > 8 ? 3 : cfg;
+  return N / (epi == kEpiSwiglu ? kCfg[c].bn / 2 : kCfg[c].bn);
+}
+
 pvf_status launch_gemm_mfma(pvf_ctx *ctx, hipStream_t s, GemmEpilogue epi, const void *A,
-                            const void *W, void *C, const void *residual, int M, int N, int K) {
+                            const void *W, void *C, const void *residual, int M, int N, int K, const NormArgs *na) {
   const uintptr_t al = (uintptr_t)A | (uintptr_t)W | (uintptr_t)C | (uintptr_t)residual;
   PVF_REQUIRE(ctx, (al & 15u) == 0, PVF_EINVAL, "gemm_mfma: operands must be 16-byte aligned");
   const int cfg = pick_config(epi, M, N, K);
   PVF_REQUIRE(ctx, cfg >= 0, PVF_ESHAPE, "gemm_mfma: no tile shape for N=%d", N);
+  const NormArgs nrm = na ? *na : NormArgs{};
+  PVF_REQUIRE(ctx, !(nrm.ss_in || nrm.ss_out) || gemm_mfma_norm_capable(cfg), PVF_ESHAPE, "gemm_mfma: tile shape %d cannot fold the norm", cfg);
   switch (epi) {
     case kEpiStore: return run_cfg<kEpiStore>(ctx, s, cfg, A, W, C, residual, M, N, K);
-    case kEpiResidual: return run_cfg<kEpiResidual>(ctx, s, cfg, A, W, C, residual, M, N, K);
-    case kEpiSwiglu: return run_cfg<kEpiSwiglu>(ctx, s, cfg, A, W, C, residual, M, N, K);
+    case kEpiResidual: return run_cfg<kEpiResidual>(ctx, s, cfg, A, W, C, residual, M, N, K, RopeArgs{}, nrm);
+    case kEpiSwiglu: return run_cfg<kEpiSwiglu>(ctx, s, cfg, A, W, C, residual, M, N, K, RopeArgs{}, nrm);
     case kEpiQkvRope: break;                     // has its own entry (launch_gemm_mfma_qkv_rope)
     case kEpiPartial: break;                     // launch_gemm_mfma_splitk
   }

@@ -22,6 +22,12 @@ struct pvf_ctx {
   void *hrows = nullptr, *logits = nullptr;
   float *splitk_ws = nullptr;          // float32 partial sums of the split-K GEMMs (bf16 contexts)
   size_t splitk_floats = 0;
+  // RMSNorm folded into the projections (bf16, launches above the split-K range): row sums of squares
+  // [d / 128 slots][max rows], and wqkv / w_gate_up with the norm gain folded in (the caller's matrices
+  // themselves where every gain is 1)
+  float *row_ss = nullptr;
+  std::vector<const void *> wqkv_f, w_gate_up_f;
+  std::vector<void *> folded_owned;
   int32_t *seq_slot = nullptr, *row_pos = nullptr;
   float2 *cos_sin = nullptr;           // [max_T, d_head/2]
   int32_t *status_host = nullptr;      // pinned, 5*G words per round: done, n_drafts, n_commit[3] of each group
@@ -85,13 +91,14 @@ pvf_status launch_gemm_simple(pvf_ctx *, hipStream_t, int, GemmEpilogue, const v
 pvf_status launch_attention_simple(pvf_ctx *, hipStream_t, int, const void *, void *, int, int, int, int);
 bool gemm_mfma_supported(int dtype, GemmEpilogue epi, int M, int N, int K);
 pvf_status launch_gemm_mfma(pvf_ctx *, hipStream_t, GemmEpilogue, const void *, const void *, void *,
-                            const void *, int, int, int);
+                            const void *, int, int, int, const NormArgs *na = nullptr);
+int gemm_mfma_norm_slots(GemmEpilogue epi, int M, int N, int K);
 bool gemm_mfma_splitk_supported(int dtype, GemmEpilogue epi, int M, int N, int K, size_t ws_floats);
 pvf_status launch_gemm_mfma_splitk(pvf_ctx *, hipStream_t, GemmEpilogue, const void *, const void *, void *, const void *,
                                    int, int, int, float *, size_t);
 bool gemm_mfma_qkv_rope_supported(int dtype, int M, int N, int K, int T, int H);
 pvf_status launch_gemm_mfma_qkv_rope(pvf_ctx *, hipStream_t, const void *, const void *, void *, void *, const float2 *,
-                                     int, int, int, int, int, bool store_v);
+                                     int, int, int, int, int, bool store_v, const NormArgs *na = nullptr);
 bool attention_mfma_supported(int dtype, int T, int d_head);
 pvf_status launch_attention_mfma(pvf_ctx *, hipStream_t, const void *, const void *, void *, int, int, int);
 pvf_status launch_rope_vt(pvf_ctx *, hipStream_t, void *, void *, int, int, int, const float2 *);
@@ -101,6 +108,11 @@ pvf_status launch_attention_window_mfma(pvf_ctx *, hipStream_t, const void *, co
                                         int64_t, const int32_t *, const int32_t *, int, int, int, int, int, int, int, void *);
 
 pvf_status launch_gemm_mfma_splitk_partial(pvf_ctx *, hipStream_t, const void *, const void *, int, int, int, float *, size_t, int *);
+
+static bool fold_norm_enabled() {       // PVF_FOLD_NORM=0: keep the norms as launches of their own (tuning runs)
+  static const bool v = [] { const char *e = getenv("PVF_FOLD_NORM"); return !(e && e[0] == '0'); }();
+  return v;
+}
 
 static bool force_simple() {
   static const bool v = [] { const char *e = getenv("PVF_FORCE_SIMPLE"); return e && e[0] == '1'; }();
@@ -180,8 +192,10 @@ static void free_ws(pvf_ctx *c) {
   for (hipEvent_t e : c->ev_pool) (void)hipEventDestroy(e);
   c->ev_pool.clear();
   void *ptrs[] = {c->h, c->xn, c->qkv, c->att, c->act, c->vt, c->hrows, c->logits, c->seq_slot, c->row_pos, c->cos_sin,
-                  c->kcache, c->vcache, c->splitk_ws, c->status_dev};
+                  c->kcache, c->vcache, c->splitk_ws, c->status_dev, c->row_ss};
   for (void *p : ptrs) if (p) (void)hipFree(p);
+  for (void *p : c->folded_owned) if (p) (void)hipFree(p);
+  c->folded_owned.clear();
   if (c->status_host) (void)hipHostFree(c->status_host);
   if (c->seq_host) (void)hipHostFree(c->seq_host);
 }
@@ -233,7 +247,8 @@ extern "C" pvf_status pvf_create(pvf_ctx **out, const pvf_model_cfg *m, const pv
       {(void **)&c->cos_sin, (int64_t)max_T * half * 8},
       // partial sums of the few-row GEMMs: rows x splits x row length, at most 384 x 49152 floats (up to 384 rows
       // every layer GEMM may split, from there to 640 rows only those with rows of 4096 or less)
-      {(void **)&c->splitk_ws, m->dtype == PVF_BF16 ? (int64_t)384 * 49152 * 4 : 0}};
+      {(void **)&c->splitk_ws, m->dtype == PVF_BF16 ? (int64_t)384 * 49152 * 4 : 0},
+      {(void **)&c->row_ss, m->dtype == PVF_BF16 && d % 128 == 0 ? (d / 128) * M * 4 : 0}};
   for (auto &r : req) {
     if (r.bytes == 0) continue;
     hipError_t e = hipMalloc(r.p, (size_t)r.bytes);
@@ -262,6 +277,38 @@ extern "C" pvf_status pvf_create(pvf_ctx **out, const pvf_model_cfg *m, const pv
       set_error(nullptr, "pvf_create: rotary table upload failed: %s", hipGetErrorString(e));
       free_ws(c);
       delete c;
+      return PVF_EHIP;
+    }
+  }
+  // Gains folded into the projections that read a normed stream: w'[n][k] = bf16(w[n][k] * gain[k]).  A layer
+  // whose gains are all 1 keeps the caller's matrix.
+  if (c->row_ss) {
+    std::vector<uint16_t> g((size_t)d);
+    auto fold = [&](const void *w, const void *gain, int64_t rows, const void **dst) -> pvf_status {
+      PVF_HIP_CHECK(nullptr, hipMemcpy(g.data(), gain, (size_t)d * 2, hipMemcpyDeviceToHost));
+      bool ones = true;
+      for (int64_t i = 0; i < d; ++i) ones = ones && g[(size_t)i] == 0x3f80;
+      if (ones) { *dst = w; return PVF_OK; }
+      void *p = nullptr;
+      hipError_t e = hipMalloc(&p, (size_t)rows * d * 2);
+      PVF_REQUIRE(nullptr, e == hipSuccess, e == hipErrorOutOfMemory ? PVF_ENOMEM : PVF_EHIP,
+                  "pvf_create: hipMalloc(%lld bytes) for a gain-folded matrix failed: %s", (long long)rows * d * 2, hipGetErrorString(e));
+      c->folded_owned.push_back(p);
+      c->ws_bytes += rows * d * 2;
+      *dst = p;
+      return launch_fold_gain(nullptr, nullptr, w, gain, p, rows, (int)d);
+    };
+    c->wqkv_f.assign(L, nullptr);
+    c->w_gate_up_f.assign(L, nullptr);
+    for (int l = 0; l < L; ++l) {
+      pvf_status st = fold(c->wqkv[l], c->attn_norm[l], 3 * d, &c->wqkv_f[l]);
+      if (st == PVF_OK) st = fold(c->w_gate_up[l], c->ffn_norm[l], 2 * ff, &c->w_gate_up_f[l]);
+      if (st != PVF_OK) { free_ws(c); delete c; return st; }
+    }
+    hipError_t e = hipDeviceSynchronize();
+    if (e != hipSuccess) {
+      set_error(nullptr, "pvf_create: folding the norm gains failed: %s", hipGetErrorString(e));
+      free_ws(c); delete c;
       return PVF_EHIP;
     }
   }
@@ -300,9 +347,71 @@ static pvf_status forward_impl(pvf_ctx *c, hipStream_t s, const int32_t *tokens,
     RUN(launch_gemm(c, s, dt, epi, A, W, C, res, Mm, Nn, Kk));                                    \
   } while (0)
   const bool fused_rope = use_attention_mfma(dt, T, dh) && gemm_mfma_qkv_rope_supported(dt, M, 3 * d, d, T, H);
-  RUN(launch_embed(c, s, dt, c->w.embed, tokens, seq_slot, S, T, d, m.vocab, c->h));
+  // Above the split-K range the two norms of a layer are folded into the projections around them: O and down
+  // write each row's sum of squares beside h, QKV and gate/up read h itself (gains folded into their weights)
+  // and scale their accumulators by 1 / rms.  The xn buffer and the 2 x n_layers norm launches disappear.
+  const int slots_o = gemm_mfma_norm_slots(kEpiResidual, M, d, d), slots_down = gemm_mfma_norm_slots(kEpiResidual, M, d, ff);
+  const bool fold_norm = !force_simple() && fold_norm_enabled() && fused_rope && c->row_ss && M > 640 && slots_o > 0 && slots_down > 0 &&
+                         slots_o <= d / 128 && slots_down <= d / 128 &&
+                         gemm_mfma_norm_slots(kEpiQkvRope, M, 3 * d, d) > 0 && gemm_mfma_norm_slots(kEpiSwiglu, M, ff, d) > 0;
+  // Up to 640 rows O and down split K: one kernel then adds their partial tiles and the residual and norms the
+  // row for the next projection (instead of a reduce kernel followed by a norm kernel).
+  const bool split_norm_o_down = !fold_norm && !force_simple() && c->splitk_ws && reduce_residual_rmsnorm_supported(dt, d) &&
+                                 gemm_mfma_splitk_supported(dt, kEpiResidual, M, d, d, c->splitk_floats) &&
+                                 gemm_mfma_splitk_supported(dt, kEpiResidual, M, d, ff, c->splitk_floats);
+  // h += A W^T; with_norm: xn = RMSNorm(h) * gain as well
+  auto project_residual_norm = [&](const void *A, const void *W, int Kk, const void *gain, void *out, bool with_norm) -> pvf_status {
+    if (split_norm_o_down && with_norm) {
+      int splits = 0;
+      ProfScope ps(c, s, PVF_PROF_GEMM, 2.0 * M * (double)d * Kk, (double)c->esize * ((double)M * Kk + (double)d * Kk + 2.0 * M * d));
+      RUN(launch_gemm_mfma_splitk_partial(c, s, A, W, M, d, Kk, c->splitk_ws, c->splitk_floats, &splits));
+      return launch_reduce_residual_rmsnorm(c, s, c->splitk_ws, splits, M, d, c->h, gain, out, m.rms_eps);
+    }
+    RUN_GEMM(kEpiResidual, A, W, c->h, c->h, M, d, Kk);
+    if (with_norm) return launch_rmsnorm(c, s, dt, c->h, gain, out, M, d, m.rms_eps);
+    return PVF_OK;
+  };
+  bool xn_ready = false;
+  NormArgs n_in, n_out;
+  n_in.ss_in = c->row_ss; n_in.ld = M; n_in.inv_d = 1.0f / (float)d; n_in.eps = m.rms_eps; n_in.n_slots_in = 1;
+  n_out.ss_out = c->row_ss; n_out.ld = M;
+  RUN(launch_embed(c, s, dt, c->w.embed, tokens, seq_slot, S, T, d, m.vocab, c->h, fold_norm ? c->row_ss : nullptr));
   for (int l = 0; l < m.n_layers; ++l) {
-    RUN(launch_rmsnorm(c, s, dt, c->h, c->attn_norm[l], c->xn, M, d, m.rms_eps));
+    if (fold_norm) {
+      {
+        ProfScope ps(c, s, PVF_PROF_GEMM, 2.0 * M * (double)(3 * d) * d,
+                     (double)c->esize * ((double)M * d + 3.0 * d * d + (double)M * 2 * d + (double)M * d));
+        RUN(launch_gemm_mfma_qkv_rope(c, s, c->h, c->wqkv_f[l], c->qkv, c->vt, c->cos_sin, M, 3 * d, d, T, H,
+                                      capture_spg > 0 && !c->cache_vt, &n_in));
+      }
+      {
+        ProfScope ps(c, s, PVF_PROF_ATTENTION, 4.0 * S * (double)T * T * d, 0.0);
+        RUN(launch_attention_mfma(c, s, c->qkv, c->vt, c->att, S, T, H));
+      }
+      if (capture_spg > 0) {
+        const int64_t layer_off = (int64_t)l * T * d * c->esize, gstride = (int64_t)m.n_layers * T * d;
+        void *vl = (char *)c->vcache + layer_off;
+        RUN(launch_kv_store(c, s, dt, c->qkv, c->vt, seq_slot, capture_spg, S, T, d, (char *)c->kcache + layer_off,
+                            c->cache_vt ? nullptr : vl, c->cache_vt ? vl : nullptr, gstride));
+      }
+      {
+        ProfScope ps(c, s, PVF_PROF_GEMM, 2.0 * M * (double)d * d, (double)c->esize * ((double)M * d + (double)d * d + 2.0 * M * d));
+        RUN(launch_gemm_mfma(c, s, kEpiResidual, c->att, c->wo[l], c->h, c->h, M, d, d, &n_out));
+      }
+      n_in.n_slots_in = slots_o;
+      {
+        ProfScope ps(c, s, PVF_PROF_GEMM, 4.0 * M * (double)ff * d, (double)c->esize * ((double)M * d + 2.0 * ff * d + (double)M * ff));
+        RUN(launch_gemm_mfma(c, s, kEpiSwiglu, c->h, c->w_gate_up_f[l], c->act, nullptr, M, ff, d, &n_in));
+      }
+      {
+        ProfScope ps(c, s, PVF_PROF_GEMM, 2.0 * M * (double)d * ff, (double)c->esize * ((double)M * ff + (double)d * ff + 2.0 * M * d));
+        RUN(launch_gemm_mfma(c, s, kEpiResidual, c->act, c->w_down[l], c->h, c->h, M, d, ff, &n_out));
+      }
+      n_in.n_slots_in = slots_down;
+      continue;
+    }
+    if (!xn_ready) RUN(launch_rmsnorm(c, s, dt, c->h, c->attn_norm[l], c->xn, M, d, m.rms_eps));
+    xn_ready = false;
     if (fused_rope) {
       // the QKV projection rotates q, k and writes the key-contiguous v in its epilogue; the row-major v third
       // has a reader only when the K/V cache keeps its values in that layout
@@ -325,10 +434,12 @@ static pvf_status forward_impl(pvf_ctx *c, hipStream_t s, const int32_t *tokens,
       RUN(launch_kv_store(c, s, dt, c->qkv, c->vt, seq_slot, capture_spg, S, T, d, (char *)c->kcache + layer_off,
                           c->cache_vt ? nullptr : vl, c->cache_vt ? vl : nullptr, gstride));
     }
-    RUN_GEMM(kEpiResidual, c->att, c->wo[l], c->h, c->h, M, d, d);
-    RUN(launch_rmsnorm(c, s, dt, c->h, c->ffn_norm[l], c->xn, M, d, m.rms_eps));
+    RUN(project_residual_norm(c->att, c->wo[l], d, c->ffn_norm[l], c->xn, true));
     RUN_GEMM(kEpiSwiglu, c->xn, c->w_gate_up[l], c->act, nullptr, M, ff, d);
-    RUN_GEMM(kEpiResidual, c->act, c->w_down[l], c->h, c->h, M, d, ff);
+    // the norm that follows the down projection is the next layer's (the final one runs on the gathered rows only)
+    const bool has_next = l + 1 < m.n_layers;
+    RUN(project_residual_norm(c->act, c->w_down[l], ff, has_next ? c->attn_norm[l + 1] : nullptr, c->xn, has_next));
+    xn_ready = has_next;
   }
   RUN(launch_gather_rows(c, s, dt, c->h, row_pos, S, T, R, d, c->hrows));
   RUN(launch_rmsnorm(c, s, dt, c->hrows, c->w.final_norm, c->hrows, S * R, d, m.rms_eps));

@@ -87,11 +87,11 @@ def test_bf16_storage_emulation_derives_the_full_width_bound(model):
     """Why 5e-2 max-abs cannot hold at d = 4096 in bf16.  (a) The float64 forward with nothing but a
     round-to-bf16 at each stored activation already sits at rms ~1.2e-2 / max ~6e-2 from the oracle: the
     bound asserted above is this figure plus margin, not a property of the kernels.  (b) The kernels
-    are no further from the oracle than that emulation is (they add nothing to the cost of bf16
-    storage), and they are closer to the emulation than two independent bf16 pipelines would be
-    (sqrt(2) x that rms); they cannot be much closer, because the first rounding that falls differently
-    (float32 accumulation order, the running maximum of the streaming softmax) changes which way
-    later roundings fall."""
+    are no further from the oracle than that emulation is: they add nothing to the cost of bf16
+    storage.  (The distance between kernels and emulation is printed only: the two round at different
+    places -- the library folds each norm into the projections around it -- and the first rounding that
+    falls differently changes which way later ones fall, so they are about as far from each other as
+    two independent bf16 pipelines.)"""
     w, ctx = model
     toks = canvases(2)
     rows = np.tile(np.arange(P, P + R, dtype=np.int32), (2, 1))
@@ -106,7 +106,6 @@ def test_bf16_storage_emulation_derives_the_full_width_bound(model):
               f"max {g_max:.4f}; GPU vs oracle rms {o_rms:.4f}", flush=True)
         assert 0.8e-2 <= e_rms <= RMS_BOUND and 4e-2 <= e_max <= MAX_BOUND    # bf16 storage alone costs this much
         assert o_rms <= 1.1 * e_rms                                           # the kernels add nothing to it
-        assert g_rms <= e_rms and g_max <= MAX_BOUND
 
 
 def spread_rows(M, n):
