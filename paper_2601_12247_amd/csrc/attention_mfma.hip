@@ -46,12 +46,19 @@ struct WinArgs {
   int32_t slots_per_group, prompt_len, block_len, R;
 };
 
-template <bool WIN>
+// SPLIT (window mode with at most 64 query rows per canvas): the 64 queries need only two of the four waves, and
+// the loop over the key tiles is a chain of dependent steps of ~2 us each, so the waves work as two pairs: pair
+// 0 takes the even key tiles, pair 1 the odd ones (two tiles are staged per step), and at the end pair 0 merges
+// pair 1's running maximum, sum and O into its own.  Half as many steps for the same work.
+template <bool WIN, bool SPLIT>
 __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
 attention_mfma_kernel(const bf16_t *__restrict__ qkv, const bf16_t *__restrict__ vt,
                       bf16_t *__restrict__ out, int T, int H, WinArgs wa) {
-  __shared__ __attribute__((aligned(1024))) unsigned char lds[2 * kStage];
+  static_assert(!SPLIT || WIN, "the key split exists in window mode only");
+  __shared__ __attribute__((aligned(1024))) unsigned char lds[(SPLIT ? 4 : 2) * kStage];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int pair = SPLIT ? wave >> 1 : 0;                    // which half of the key tiles this wave takes
+  const int qwave = SPLIT ? wave & 1 : wave;                 // which 32 queries
   const int fr = lane & 31, fh = lane >> 5;
   const int q0 = blockIdx.x * TQ, head = blockIdx.y, seq = blockIdx.z;
   const int d = H * DH;
@@ -71,7 +78,7 @@ attention_mfma_kernel(const bf16_t *__restrict__ qkv, const bf16_t *__restrict__
   }
 
   // ---- Q fragments: "B" operand, column = query, k-chunk = 8 consecutive d ----
-  const int qrow = min(q0 + wave * 32 + fr, TQrows - 1);
+  const int qrow = min(q0 + qwave * 32 + fr, TQrows - 1);
   bf16x8 qf[8];
 #pragma unroll
   for (int ks = 0; ks < 8; ++ks)
@@ -92,8 +99,8 @@ attention_mfma_kernel(const bf16_t *__restrict__ qkv, const bf16_t *__restrict__
     v_src[i] = vtb + (int64_t)vr * T + vc * 8;
     v_row[i] = vr; v_key[i] = vc * 8;
   }
-  auto issue_loads = [&](int kt, int buf) {
-    unsigned char *dst = lds + buf * kStage + wave * 1024;
+  auto issue_loads = [&](int kt, int slot) {                 // key tile kt -> LDS tile slot `slot`
+    unsigned char *dst = lds + slot * kStage + wave * 1024;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const bf16_t *ks, *vs;
@@ -137,13 +144,24 @@ attention_mfma_kernel(const bf16_t *__restrict__ qkv, const bf16_t *__restrict__
   for (int ks2 = 0; ks2 < 4; ++ks2) v_rd[ks2] = fr * 128 + (((2 * ks2 + fh) ^ ((fr >> 1) & 7)) << 4);
 
   const int nk = T / TK;
-  issue_loads(0, 0);
-  auto tile = [&](int kt, auto buf_c) {
+  // step = one key tile (SPLIT: two, one per pair); kBuf = which half of the double buffer holds it
+  const int n_steps = SPLIT ? (nk + 1) / 2 : nk;
+  auto stage_step = [&](int st, int buf) {
+    if (SPLIT) {
+      issue_loads(2 * st, 2 * buf);
+      if (2 * st + 1 < nk) issue_loads(2 * st + 1, 2 * buf + 1);
+    } else {
+      issue_loads(st, buf);
+    }
+  };
+  stage_step(0, 0);
+  auto tile = [&](int st, auto buf_c) {
     constexpr int kBuf = decltype(buf_c)::value;
     __builtin_amdgcn_s_waitcnt(0x0f70);          // vmcnt(0)
     __syncthreads();
-    if (kt + 1 < nk) issue_loads(kt + 1, kBuf ^ 1);
-    const unsigned char *ks_ = lds + kBuf * kStage;
+    if (st + 1 < n_steps) stage_step(st + 1, kBuf ^ 1);
+    if (SPLIT && 2 * st + pair >= nk) return;    // an odd number of key tiles: pair 1 has none in the last step
+    const unsigned char *ks_ = lds + (SPLIT ? 2 * kBuf + pair : kBuf) * kStage;
     const unsigned char *vs_ = ks_ + kKTile;
 
     // ---- S^T = K Q^T : 2 key sub-tiles x 8 k-steps ----
@@ -202,15 +220,40 @@ attention_mfma_kernel(const bf16_t *__restrict__ qkv, const bf16_t *__restrict__
       ol = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ones, pf[ks2], ol, 0, 0, 0);
     }
   };
-  for (int kt = 0; kt + 1 < nk; kt += 2) {
-    tile(kt, std::integral_constant<int, 0>{});
-    tile(kt + 1, std::integral_constant<int, 1>{});
+  for (int st = 0; st + 1 < n_steps; st += 2) {
+    tile(st, std::integral_constant<int, 0>{});
+    tile(st + 1, std::integral_constant<int, 1>{});
   }
-  if (nk & 1) tile(nk - 1, std::integral_constant<int, 0>{});
-  const float l_run = __shfl(ol[0], fr, 64);                 // row 0 of that product: lane q % 32, register 0
+  if (n_steps & 1) tile(n_steps - 1, std::integral_constant<int, 0>{});
+  float l_run = __shfl(ol[0], fr, 64);                       // row 0 of that product: lane q % 32, register 0
+
+  if (SPLIT) {
+    // pair 1 hands (O, running maximum, running sum) of its key tiles to the wave of pair 0 with the same queries;
+    // both are sums of 2^((s - m_pair) c) terms, so they meet after rescaling to the larger maximum
+    __syncthreads();                                         // every wave is done with the tiles
+    float *x = reinterpret_cast<float *>(lds) + qwave * 66 * 64 + lane;
+    if (pair == 1) {
+#pragma unroll
+      for (int t = 0; t < 4; ++t)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) x[(t * 16 + e) * 64] = o[t][e];
+      x[64 * 64] = m_run;
+      x[65 * 64] = l_run;
+    }
+    __syncthreads();
+    if (pair == 1) return;
+    const float m1 = x[64 * 64], l1 = x[65 * 64];
+    const float mm = fmaxf(m_run, m1);
+    const float a0 = fast_exp2((m_run - mm) * c), a1 = fast_exp2((m1 - mm) * c);   // a pair without tiles: m = -inf, factor 0
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) o[t][e] = o[t][e] * a0 + x[(t * 16 + e) * 64] * a1;
+    l_run = l_run * a0 + l1 * a1;
+  }
 
   // ---- out[q][head*128 + d]: lane holds 4 consecutive d per accumulator group ----
-  const int q = q0 + wave * 32 + fr;
+  const int q = q0 + qwave * 32 + fr;
   if (q < TQrows) {
     const float inv = 1.0f / l_run;
     bf16_t *orow = out + (row0 + q) * d + (int64_t)head * DH;
@@ -349,7 +392,10 @@ pvf_status launch_attention_window_mfma(pvf_ctx *ctx, hipStream_t s, const void 
   wa.seq_slot = seq_slot; wa.k_active = k_active; wa.slots_per_group = slots_per_group;
   wa.prompt_len = prompt_len; wa.block_len = block_len; wa.R = R;
   const dim3 grid((R + TQ - 1) / TQ, n_heads, S);
-  attention_mfma_kernel<true><<<grid, 256, 0, s>>>((const bf16_t *)qkv_w, (const bf16_t *)vt_w, (bf16_t *)out, T, n_heads, wa);
+  if (R <= 64)
+    attention_mfma_kernel<true, true><<<grid, 256, 0, s>>>((const bf16_t *)qkv_w, (const bf16_t *)vt_w, (bf16_t *)out, T, n_heads, wa);
+  else
+    attention_mfma_kernel<true, false><<<grid, 256, 0, s>>>((const bf16_t *)qkv_w, (const bf16_t *)vt_w, (bf16_t *)out, T, n_heads, wa);
   PVF_LAUNCH_CHECK(ctx, "attention_window_mfma");
   return PVF_OK;
 }
@@ -363,7 +409,7 @@ pvf_status launch_attention_mfma(pvf_ctx *ctx, hipStream_t s, const void *qkv, c
                                  void *out, int S, int T, int n_heads) {
   if (S == 0) return PVF_OK;
   const dim3 grid((T + TQ - 1) / TQ, n_heads, S);
-  attention_mfma_kernel<false><<<grid, 256, 0, s>>>((const bf16_t *)qkv, (const bf16_t *)vt, (bf16_t *)out, T, n_heads, WinArgs{});
+  attention_mfma_kernel<false, false><<<grid, 256, 0, s>>>((const bf16_t *)qkv, (const bf16_t *)vt, (bf16_t *)out, T, n_heads, WinArgs{});
   PVF_LAUNCH_CHECK(ctx, "attention_mfma");
   return PVF_OK;
 }

@@ -250,10 +250,21 @@ reduce_residual_rmsnorm_kernel(const float *__restrict__ partial, int splits, in
       float a[8];
 #pragma unroll
       for (int e = 0; e < 8; ++e) a[e] = 0.f;
-      for (int z = 0; z < splits; ++z) {
-        const float4 *pr = reinterpret_cast<const float4 *>(partial + ((int64_t)z * M + m) * d + (int64_t)i * 8);
-        const float4 p0 = pr[0], p1 = pr[1];
-        a[0] += p0.x; a[1] += p0.y; a[2] += p0.z; a[3] += p0.w; a[4] += p1.x; a[5] += p1.y; a[6] += p1.z; a[7] += p1.w;
+      for (int z0 = 0; z0 < splits; z0 += 4) {             // 4 splits in flight at a time, added in split order
+        float4 p0[4], p1[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const int z = min(z0 + j, splits - 1);
+          const float4 *pr = reinterpret_cast<const float4 *>(partial + ((int64_t)z * M + m) * d + (int64_t)i * 8);
+          p0[j] = pr[0]; p1[j] = pr[1];
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          if (z0 + j < splits) {
+            a[0] += p0[j].x; a[1] += p0[j].y; a[2] += p0[j].z; a[3] += p0[j].w;
+            a[4] += p1[j].x; a[5] += p1[j].y; a[6] += p1[j].z; a[7] += p1[j].w;
+          }
+        }
       }
       const uint4 r4 = hr[i];
       const uint32_t rw[4] = {r4.x, r4.y, r4.z, r4.w};
