@@ -152,7 +152,11 @@ typedef struct {
   uint32_t *cal_m;      /*              candidate token is v: n_v (events), m_v (events     */
   uint32_t *cal_a;      /*              with a non-empty impact set), sum of A_j, and       */
   double  *cal_vig;     /* [vocab]      sum of VIG_j = A_j * Delta H_j.  The caller zeroes  */
-                        /*              them before the first round.                        */
+                        /*              them before the first round.  The three counters    */
+                        /*              are exact; cal_vig is added with float64 atomics,   */
+                        /*              so when several events of one round carry the same  */
+                        /*              token the order of the adds, and with it the last   */
+                        /*              bits of that sum, is not fixed.                     */
 } pvf_state;
 
 typedef struct {

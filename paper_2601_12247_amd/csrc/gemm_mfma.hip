@@ -114,7 +114,11 @@ gemm_bf16_mfma_kernel(const bf16_t *__restrict__ A, const bf16_t *__restrict__ W
   constexpr int CPR = BK / 8;                        // 16-byte chunks per LDS row
   constexpr int RPI = kThreads / CPR;                // tile rows covered by one load instruction of the block
   constexpr int kInstrBytes = kThreads * 16;         // LDS bytes filled by one load instruction of the block
-  constexpr int LA = BM / RPI, LW = BN / RPI;        // direct loads per thread per stage
+  // A tile of 2.5 x RPI rows (160 x 256): the last A load instruction fills rows only from the lower half of the
+  // block; the waves of the upper half repeat their previous load (same bytes to the same slot), so that every wave
+  // has the same number of loads in flight and the same wait counts.
+  constexpr bool kHalfA = BM % RPI != 0;
+  constexpr int LA = (BM + RPI - 1) / RPI, LW = BN / RPI;        // direct loads per thread per stage
   constexpr int KS = BK / 32;                        // MFMA k-steps per stage
   constexpr int kRowBytes = BK * 2;
   // With a ring of only two stages the refill of a slot is issued as soon as the slot is free (right
@@ -123,7 +127,7 @@ gemm_bf16_mfma_kernel(const bf16_t *__restrict__ A, const bf16_t *__restrict__ W
   // of the slot freed one stage ago over the first k-steps of a stage.
   constexpr bool kLate = kStages == 2;
   constexpr int kAhead = kLate ? kStages : kStages - 1;     // stages in flight after the prologue
-  static_assert(BM % RPI == 0 && BN % RPI == 0 && BK == 64 && BM % (16 * WM) == 0 && BN % (32 * WN) == 0, "tile shape");
+  static_assert(BM % (RPI / 2) == 0 && (!kHalfA || LA >= 2) && BN % RPI == 0 && BK == 64 && BM % (16 * WM) == 0 && BN % (32 * WN) == 0, "tile shape");
   static_assert((EPI != kEpiQkvRope && EPI != kEpiSwiglu) || BM % (32 * WM) == 0, "the rotary and SwiGLU epilogues take whole 32-row passes");
   static_assert(EPI != kEpiSwiglu || NT16 % 4 == 0, "SwiGLU pairs 32-column gate/up groups inside a wave");
   extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
@@ -167,9 +171,10 @@ gemm_bf16_mfma_kernel(const bf16_t *__restrict__ A, const bf16_t *__restrict__ W
   auto issue_one = [&](int kt, int i) {                      // load i (A loads first, then W) of stage kt
     unsigned char *dst = lds + (kt % kStages) * kStage + wave * 1024;
     const size_t koff = (size_t)kt * (BK * 2);
-    if (i < LA)
-      __builtin_amdgcn_global_load_lds((gptr_t *)(Ab + koff + a_off[i]), (lptr_t *)(dst + i * kInstrBytes), 16, 0, 0);
-    else
+    if (i < LA) {
+      const int ia = (kHalfA && i == LA - 1 && wave >= WM * WN / 2) ? i - 1 : i;      // uniform
+      __builtin_amdgcn_global_load_lds((gptr_t *)(Ab + koff + a_off[ia]), (lptr_t *)(dst + ia * kInstrBytes), 16, 0, 0);
+    } else
       __builtin_amdgcn_global_load_lds((gptr_t *)(Wb + koff + w_off[i - LA]), (lptr_t *)(dst + kATile + (i - LA) * kInstrBytes), 16, 0, 0);
   };
 
@@ -575,7 +580,7 @@ pvf_status run(pvf_ctx *ctx, hipStream_t s, const void *A, const void *W, void *
 }
 
 struct TileCfg { int bm, bn, bk, stages; double eff; bool plain_only; };
-constexpr int kNumCfg = 9;
+constexpr int kNumCfg = 10;
 // Every shape for many rows runs 8 waves, two per SIMD (the two small ones 4 waves, two workgroups per CU):
 // with one wave per SIMD the 256 x 256 tile (wave tiles of 128 x 128, a third fewer LDS reads) measured 2-4 %
 // slower, smaller wave tiles far slower.
@@ -589,7 +594,8 @@ constexpr TileCfg kCfg[kNumCfg] = {
     {320, 128, 64, 2, 0.78, true},    // 2560 rows = 8 tile rows: with N = 4096 exactly one tile per CU (wave tiles 80 x 64)
     {64, 64, 64, 5, 0.0, true},       // few rows (window forward of the K/V-cached rounds): the GEMM streams the weights,
     {64, 128, 64, 3, 0.0, false},     // so many small workgroups with deep rings; chosen by pick_config for M <= 384
-    {192, 128, 64, 3, 0.86, true}};   // 1536 rows = 8 tile rows: with N = 4096 one tile per CU
+    {192, 128, 64, 3, 0.86, true},    // 1536 rows = 8 tile rows: with N = 4096 one tile per CU
+    {160, 256, 64, 3, 0.85, true}};   // 2560 rows = 16 tile rows: one tile per CU like 320 x 128, with room for a third stage
 
 template <int EPI>
 pvf_status run_cfg(pvf_ctx *ctx, hipStream_t s, int cfg, const void *A, const void *W, void *C,
@@ -604,6 +610,7 @@ pvf_status run_cfg(pvf_ctx *ctx, hipStream_t s, int cfg, const void *A, const vo
     case 6: if constexpr (kPlain) return run<EPI, 64, 64, 64, 5, 2, 2>(ctx, s, A, W, C, Res, M, N, K, ra, SplitK{nullptr, 0}, 1, na); break;
     case 7: return run<EPI, 64, 128, 64, 3, 2, 2>(ctx, s, A, W, C, Res, M, N, K, ra, SplitK{nullptr, 0}, 1, na);
     case 8: if constexpr (kPlain) return run<EPI, 192, 128, 64, 3, 2, 4>(ctx, s, A, W, C, Res, M, N, K, ra, SplitK{nullptr, 0}, 1, na); break;
+    case 9: if constexpr (kPlain) return run<EPI, 160, 256, 64, 3, 2, 4>(ctx, s, A, W, C, Res, M, N, K, ra, SplitK{nullptr, 0}, 1, na); break;
     default: break;
   }
   return run<EPI, 128, 128, 64, 3, 4, 2>(ctx, s, A, W, C, Res, M, N, K, ra, SplitK{nullptr, 0}, 1, na);
@@ -798,7 +805,7 @@ int gemm_mfma_norm_slots(GemmEpilogue epi, int M, int N, int K) {
   if (!gemm_mfma_supported(PVF_BF16, epi, M, N, K)) return 0;
   const int cfg = pick_config(epi, M, N, K);
   if (!gemm_mfma_norm_capable(cfg)) return 0;
-  const int c = cfg == 3 || cfg > 8 ? 3 : cfg;
+  const int c = cfg == 3 || cfg >= kNumCfg ? 3 : cfg;
   return N / (epi == kEpiSwiglu ? kCfg[c].bn / 2 : kCfg[c].bn);
 }
 

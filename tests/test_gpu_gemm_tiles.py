@@ -40,6 +40,6 @@ def run_child(tile):
 def test_all_tile_shapes_agree_bit_for_bit():
     want = run_child("")                           # the shapes the cost model picks
     assert len(want) == 3
-    for tile in range(9):
+    for tile in range(10):
         got = run_child(str(tile))
         assert got == want, f"tile shape {tile} differs from the default choice"
