@@ -589,7 +589,7 @@ constexpr int kNumCfg = 10;
 constexpr TileCfg kCfg[kNumCfg] = {
     {256, 256, 64, 2, 1.00, false},   // the wide layers
     {128, 256, 64, 3, 0.89, false}, {256, 128, 64, 3, 0.885, false},
-    {128, 128, 64, 3, 0.70, false},   // launches of a single round of tiles: the smallest area finishes first
+    {128, 128, 64, 5, 0.70, false},   // launches of a single round of tiles: the smallest area finishes first
     {192, 256, 64, 2, 0.93, false},   // fills the chip when M / 256 leaves many CUs idle
     {320, 128, 64, 2, 0.78, true},    // 2560 rows = 8 tile rows: with N = 4096 exactly one tile per CU (wave tiles 80 x 64)
     {64, 64, 64, 5, 0.0, true},       // few rows (window forward of the K/V-cached rounds): the GEMM streams the weights,
@@ -613,7 +613,7 @@ pvf_status run_cfg(pvf_ctx *ctx, hipStream_t s, int cfg, const void *A, const vo
     case 9: if constexpr (kPlain) return run<EPI, 160, 256, 64, 3, 2, 4>(ctx, s, A, W, C, Res, M, N, K, ra, SplitK{nullptr, 0}, 1, na); break;
     default: break;
   }
-  return run<EPI, 128, 128, 64, 3, 4, 2>(ctx, s, A, W, C, Res, M, N, K, ra, SplitK{nullptr, 0}, 1, na);
+  return run<EPI, 128, 128, 64, 5, 4, 2>(ctx, s, A, W, C, Res, M, N, K, ra, SplitK{nullptr, 0}, 1, na);
 }
 
 // Tile shape: the one with the least estimated time = rounds of workgroups over the 256 CUs
@@ -740,7 +740,7 @@ pvf_status launch_gemm_mfma_splitk_partial(pvf_ctx *ctx, hipStream_t s, const vo
   PVF_REQUIRE(ctx, splits >= 1 && ws != nullptr, PVF_ESHAPE, "gemm_mfma: no split-K plan for M=%d N=%d K=%d", M, Nw, K);
   const SplitK sk{ws, K / 64 / splits};
   *splits_out = splits;
-  if (tile == 3) return run<kEpiPartial, 128, 128, 64, 3, 4, 2>(ctx, s, A, W, nullptr, nullptr, M, Nw, K, RopeArgs{}, sk, splits);
+  if (tile == 3) return run<kEpiPartial, 128, 128, 64, 5, 4, 2>(ctx, s, A, W, nullptr, nullptr, M, Nw, K, RopeArgs{}, sk, splits);
   if (tile == 7) return run<kEpiPartial, 64, 128, 64, 3, 2, 2>(ctx, s, A, W, nullptr, nullptr, M, Nw, K, RopeArgs{}, sk, splits);
   if (tile == 8) return run<kEpiPartial, 192, 128, 64, 3, 2, 4>(ctx, s, A, W, nullptr, nullptr, M, Nw, K, RopeArgs{}, sk, splits);
   return run<kEpiPartial, 320, 128, 64, 2, 4, 2>(ctx, s, A, W, nullptr, nullptr, M, Nw, K, RopeArgs{}, sk, splits);
