@@ -45,8 +45,8 @@ CONSISTENT_MIX, CONSISTENT_SCALE = 1.0, 12.0   # self-consistent model: K=0 deco
 # HBM-side bytes per launch (L2 fills + write-backs) from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE passes over
 # this script, scaled by what the counters read for a plain 256 MiB copy; the passes and the arithmetic are in
 # profiles/bench_c3_llada8b_pmc_hbm_traffic.txt
-TRAFFIC_GEMM = 412.0e6         # mean over the GEMM launches of the timed mix (algorithmic: 179.4e6)
-TRAFFIC_STAGE1 = 518.5e6       # [2048, 126464] bf16 logits (algorithmic: 518.0e6)
+TRAFFIC_GEMM = 411.0e6         # mean over the GEMM launches of the timed mix (algorithmic: 178.8e6)
+TRAFFIC_STAGE1 = 518.6e6       # [2048, 126464] bf16 logits (algorithmic: 518.0e6)
 
 # full-batch forwards: sequences per forward, canvas length, window rows per canvas
 FULL_BATCH = {"c3_5x512": (5, 512, 64), "c4_9x1280": (9, 1280, 128), "c5_80x1024": (80, 1024, 64)}
