@@ -8,8 +8,8 @@
 //     v_mfma_f32_16x16x32_bf16 tiles (in a loop that also feeds LDS and direct loads this shape
 //     sustains ~14% more than 32x32x16 at two waves per SIMD, although a loop of nothing but
 //     MFMAs runs both at the same rate).  The shapes in use: 256 x 256 with 8 waves (2 x 4) for the
-//     wide layers; 192 x 256, 128 x 256, 256 x 128, 320 x 128, 192 x 128 and 128 x 128, also with 8
-//     waves, where they put (nearly) one tile on every CU; 64 x 64 and 64 x 128 with 4 waves for
+//     wide layers; 192 x 256, 128 x 256, 256 x 128, 160 x 256, 320 x 128, 192 x 128 and 128 x 128, also
+//     with 8 waves, where they put (nearly) one tile on every CU; 64 x 64 and 64 x 128 with 4 waves for
 //     launches with few rows, which stream the weights and want many workgroups with deep rings
 //     (pick_config); launches of up to 640 rows may also split K over several workgroups per tile;
 //   * both operands are K-contiguous in memory, so a 16-byte chunk is 8 consecutive k of one
@@ -17,7 +17,9 @@
 //     of 64-byte pieces) through a ring of LDS buffers; tiles go from
 //     global memory straight into LDS (global_load_lds_dwordx4, no register staging) ahead of
 //     the MFMAs; one raw s_barrier per stage, preceded by an explicit s_waitcnt vmcnt(n) that
-//     lets the loads of later stages stay in flight;
+//     lets the loads of later stages stay in flight.  The ring is as deep as the 160 KB of LDS
+//     allow (two stages of the 256 x 256 tile, three of 160 x 256, five of 128 x 128): where a
+//     stage lasts well under a microsecond the second stage of look-ahead is worth 10-15 %;
 //   * an LDS row is 128 bytes (8 chunks); the chunk position is XOR-swizzled with
 //     (row >> 1) & 7 so that the ds_read_b128 of an MFMA operand (16 consecutive rows, 4 chunk
 //     positions) touches every bank once per 16 lanes.  The swizzle is applied by choosing
