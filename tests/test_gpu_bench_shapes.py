@@ -9,7 +9,9 @@ the MFMA attention) differ from those a 512-row launch selects, so they are chec
   * the fused QKV epilogue against float64 directly: whole rows of rotated q | rotated k | v, and the
     whole key-contiguous copy of v;
   * every layer GEMM on whole rows and whole columns that cross every tile of every grid;
-  * the bf16-storage emulation (tests/bf16_emulation.py) as the derivation of the full-width bound.
+  * the bf16-storage emulation (tests/bf16_emulation.py) as the derivation of the full-width bound;
+  * the same 2-layer model forwarded as 9 x 1280 and 80 x 1024 canvases (the larger full-batch forwards the
+    benchmark times), a few canvases of each against oracle.forward.
 """
 import numpy as np
 import pytest
@@ -32,10 +34,15 @@ RMS_BOUND, MAX_BOUND = 1.5e-2, 8e-2
 
 
 @pytest.fixture(scope="module")
-def model():
+def weights():
     w = S.make_weights(SHAPE, seed=21, round_to_bf16=True)
-    ctx = make_context(SHAPE, to_device(w, torch.bfloat16), max_seqs=5, max_T=T, max_rows=R)
-    return w, ctx
+    return w, to_device(w, torch.bfloat16)
+
+
+@pytest.fixture(scope="module")
+def model(weights):
+    w, w_dev = weights
+    return w, make_context(SHAPE, w_dev, max_seqs=5, max_T=T, max_rows=R)
 
 
 def canvases(n):
@@ -106,6 +113,46 @@ def test_bf16_storage_emulation_derives_the_full_width_bound(model):
               f"max {g_max:.4f}; GPU vs oracle rms {o_rms:.4f}", flush=True)
         assert 0.8e-2 <= e_rms <= RMS_BOUND and 4e-2 <= e_max <= MAX_BOUND    # bf16 storage alone costs this much
         assert o_rms <= 1.1 * e_rms                                           # the kernels add nothing to it
+
+
+def big_canvases(n, T_, P_, seed):
+    """n canvases of T_ tokens: one prompt + masks with a few committed tokens, the others differing in 1..3 fills."""
+    base = np.full(T_, SHAPE.mask_id, dtype=np.int32)
+    base[:P_] = S.make_prompt(seed, P_, V, SHAPE.mask_id)
+    base[P_:P_ + 5] = S.make_prompt(seed + 1, 5, V, SHAPE.mask_id)
+    fills = S.make_prompt(seed + 2, 3 * n, V, SHAPE.mask_id)
+    out = np.tile(base, (n, 1))
+    for j in range(1, n):
+        k = 1 + j % 3
+        out[j, P_ + 7 + 3 * np.arange(k)] = fills[3 * j:3 * j + k]
+    return out
+
+
+@pytest.mark.parametrize("n_seq,T_,P_,R_,check", [(9, 1280, 256, 128, (0, 8)), (80, 1024, 512, 64, (37, 79))])
+def test_two_layer_full_width_forward_at_the_larger_configurations(weights, n_seq, T_, P_, R_, check):
+    """9 x 1280 (M = 11 520) and 80 x 1024 (M = 81 920), the two larger full-batch forwards the benchmark times:
+    every projection runs 256 x 256 tiles over many rounds there (O and down too, with 16 slots of folded-norm
+    sums), attention has 10 / 8 query tiles per head.  Window logits of two canvases of each against the oracle,
+    same bound as at 5 x 512."""
+    w, w_dev = weights
+    ctx = make_context(SHAPE, w_dev, max_seqs=n_seq, max_T=T_, max_rows=R_)
+    toks = big_canvases(n_seq, T_, P_, seed=41)
+    rows = np.tile(np.arange(P_, P_ + R_, dtype=np.int32), (n_seq, 1))
+    got = ctx.forward(torch.from_numpy(toks).cuda(), torch.from_numpy(rows).cuda()).float().cpu().numpy()
+    del ctx
+    torch.cuda.empty_cache()
+    for s in check:
+        want = O.forward(toks[s], w, oracle_model_cfg(SHAPE), rows=rows[s])
+        diff = got[s] - want
+        rms, err = float(np.sqrt(np.mean(diff ** 2))), float(np.abs(diff).max())
+        print(f"{n_seq} x {T_} canvas {s}: rms {rms:.4f} max {err:.4f} (logit std {want.std():.3f})", flush=True)
+        assert abs(float(diff.mean())) <= 1e-3
+        assert rms <= RMS_BOUND and err <= MAX_BOUND
+        _, t = O.stage1(want, 1.0, SHAPE.mask_id)
+        _, tg = O.stage1(got[s], 1.0, SHAPE.mask_id)
+        top2 = np.sort(np.delete(want, SHAPE.mask_id, axis=1), axis=1)[:, -2:]
+        clear = (top2[:, 1] - top2[:, 0]) > 2 * err
+        assert clear.sum() >= 8 and np.array_equal(t[clear], tg[clear])
 
 
 def spread_rows(M, n):
