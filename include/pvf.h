@@ -33,6 +33,12 @@
  *   - Working set B_t: the active block; with n_sparse = N_s > 0 also the whole next block
  *     once the active block holds at most N_s masks (App. A.4.1, Eq. block_expansion).
  *     Impact set, compatibility, C_total, commits and candidates all range over B_t.
+ *   - Environment variables, each read once per process; none is needed in normal use:
+ *     PVF_GEMM_TILE=<n>   force bf16 GEMM tile shape n wherever a launch can take it
+ *                         (tile sweeps; every shape gives bit-identical results),
+ *     PVF_FORCE_SIMPLE=1  run bf16 launches on the plain (non-MFMA) kernels,
+ *     PVF_FOLD_NORM=0     keep every RMSNorm a launch of its own instead of folding it
+ *                         into the projections around it (forwards above 640 rows).
  */
 #ifndef PVF_H
 #define PVF_H
