@@ -742,6 +742,9 @@ pvf_status launch_gemm_mfma_splitk_partial(pvf_ctx *ctx, hipStream_t s, const vo
   PVF_REQUIRE(ctx, splits >= 1 && ws != nullptr, PVF_ESHAPE, "gemm_mfma: no split-K plan for M=%d N=%d K=%d", M, Nw, K);
   const SplitK sk{ws, K / 64 / splits};
   *splits_out = splits;
+  // 193-384 rows: two (three) tile rows of 160 x 256 where the width allows it -- as many tiles as 320 x 128 and room for
+  // a third stage, which these latency-bound launches want more than they mind fetching each weight tile twice from L2
+  if (tile == 5 && Nw % 256 == 0) return run<kEpiPartial, 160, 256, 64, 3, 2, 4>(ctx, s, A, W, nullptr, nullptr, M, Nw, K, RopeArgs{}, sk, splits);
   if (tile == 3) return run<kEpiPartial, 128, 128, 64, 5, 4, 2>(ctx, s, A, W, nullptr, nullptr, M, Nw, K, RopeArgs{}, sk, splits);
   if (tile == 7) return run<kEpiPartial, 64, 128, 64, 3, 2, 2>(ctx, s, A, W, nullptr, nullptr, M, Nw, K, RopeArgs{}, sk, splits);
   if (tile == 8) return run<kEpiPartial, 192, 128, 64, 3, 2, 4>(ctx, s, A, W, nullptr, nullptr, M, Nw, K, RopeArgs{}, sk, splits);
